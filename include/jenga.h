@@ -1,0 +1,246 @@
+/*
+ * jenga.h -- C ABI of the MI355X paged-decode hot path behind a heterogeneous
+ * (multi layer type) KV-cache memory manager.
+ *
+ * Two halves:
+ *   host   a two-level page allocator over one device memory pool: equal large
+ *          pages whose size is a common multiple (normally the least one) of
+ *          every layer type's small-page size, split on demand into small pages
+ *          of one type, placed request-aware (paper Sec. 4.1, 4.3), plus the
+ *          per-request page lists that become per-layer-type block tables
+ *          (Sec. 4.2 item 2).  Never touches device memory.
+ *   device HIP kernels for gfx950 that append one token's K/V into its page and
+ *          run batched single-token decode attention through a layer type's
+ *          block table (the kernel view of Sec. 4.2: start pointer, page size,
+ *          page ids).
+ *
+ * Conventions
+ *   - every function returns JENGA_OK (0) or a negative jenga_status; nothing
+ *     throws across the boundary; jenga_strerror() names a status;
+ *   - "host" pointers are ordinary process memory, "device" pointers are HIP
+ *     device memory of the current device; the library never allocates, frees or
+ *     copies device memory and never synchronises a stream;
+ *   - host calls on one pool are not thread safe (the caller serialises them, as
+ *     a serving engine's single scheduler thread does);
+ *   - device calls validate what the host can see, enqueue their kernels on
+ *     `stream` and return; the caller orders them (append before decode on the
+ *     same stream) and keeps every buffer alive until the stream has run them.
+ *
+ * Address map (all sizes in bytes; e = element size of the kind's dtype)
+ *   small page `sid` of kind k starts at   device_base + sid * small_page_bytes[k]
+ *   layer `l` of the kind inside it at      + l * slice,  slice = 2 * n_kv_heads * T * D * e
+ *   KV head h inside the layer slice at     + h * (2 * T * D * e)
+ *   K rows first, then V rows               + (is_v ? T * D * e : 0)
+ *   token t of the page, element d          + (t * D + d) * e
+ *   (page-layer partition of Sec. 4.2; the order inside a layer slice is this
+ *   library's choice, the paper leaves it open.)
+ */
+#ifndef JENGA_H
+#define JENGA_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct jenga_pool jenga_pool;   /* opaque host object */
+typedef void* jenga_stream;             /* a hipStream_t, or NULL for the null stream */
+
+typedef enum {
+  JENGA_OK = 0,
+  JENGA_ERR_INVALID = -1,    /* bad argument, unknown id, double free, wrong kind type */
+  JENGA_ERR_OOM = -2,        /* allocation steps 1-3 all failed (no eviction on this path) */
+  JENGA_ERR_ALIGN = -3,      /* a pointer or size is not 16-byte aligned */
+  JENGA_ERR_WORKSPACE = -4,  /* split-K workspace too small */
+  JENGA_ERR_HIP = -5,        /* a HIP runtime call failed */
+  JENGA_ERR_UNSUPPORTED = -6 /* shape outside what the kernels are built for */
+} jenga_status;
+
+typedef enum { JENGA_F32 = 0, JENGA_BF16 = 1 } jenga_dtype;
+
+typedef enum {
+  JENGA_FULL = 0,    /* attends to every cached token */
+  JENGA_WINDOW = 1,  /* attends to the last `window` tokens, the newest included (Sec. 3.1 a, 5.1) */
+  JENGA_CROSS = 2,   /* fixed encoder (image) K/V, written once, no append (Sec. 3.1 c) */
+  JENGA_OPAQUE = 3   /* pages the kernels never read, e.g. a state-space layer's state (Sec. 3.1 b) */
+} jenga_kind_type;
+
+/* One layer type ("kind").  For attention kinds a small page holds tokens_per_page
+ * tokens for all n_layers layers of the kind (Sec. 4.1 footnote, Sec. 4.2). */
+typedef struct {
+  int32_t type;             /* jenga_kind_type */
+  int32_t dtype;            /* jenga_dtype of K/V (and of q, k_new, v_new) */
+  int32_t n_layers;         /* >= 1 */
+  int32_t n_kv_heads;       /* attention kinds: >= 1 */
+  int32_t head_dim;         /* attention kinds: 64, 128 or 256 */
+  int32_t tokens_per_page;  /* attention kinds: power of two in [8, 128]; OPAQUE: 1 */
+  int32_t window;           /* WINDOW kinds: > 0; others: 0 */
+  int32_t reserved;         /* 0 */
+  int64_t small_page_bytes; /* 0: n_layers * slice for attention kinds; otherwise at least that,
+                               and a multiple of 16.  OPAQUE kinds must give it. */
+} jenga_kind_desc;
+
+typedef struct {
+  int64_t large_page_bytes;
+  int64_t n_large_pages;
+  int64_t free_large_pages;
+  int32_t n_kinds;
+  int32_t reserved;
+} jenga_pool_info;
+
+typedef struct {
+  int64_t small_page_bytes;
+  int64_t slice_bytes;        /* one layer's part of a small page (0 for OPAQUE) */
+  int64_t small_per_large;    /* r_k = large_page_bytes / small_page_bytes */
+  int64_t owned_large_pages;  /* large pages currently split into pages of this kind */
+  int64_t used_small_pages;   /* reference count > 0 */
+  int64_t unused_small_pages; /* inside owned large pages: internal fragmentation (Sec. 4.3, 4.4) */
+} jenga_kind_stats;
+
+/* ------------------------------------------------------------------ host: pool */
+
+/* Least common multiple of the kinds' small-page sizes: the compatible page size of
+ * Sec. 1 / Sec. 4.1 (2 KB, 3 KB -> 6 KB; 256, 384 -> 768).  kinds: host array.
+ * Errors: INVALID (bad descriptor), ALIGN, UNSUPPORTED (overflow of int64). */
+int jenga_lcm_page_bytes(const jenga_kind_desc* kinds, int32_t n_kinds, int64_t* out_bytes);
+
+/* Create the allocator over [device_base, device_base + pool_bytes).  The pool is cut
+ * into floor(pool_bytes / large_page_bytes) large pages, all free (Sec. 4.1).
+ * large_page_bytes must be a positive common multiple of every kind's small-page size
+ * (pass jenga_lcm_page_bytes() for the paper's choice).  device_base is borrowed, must be
+ * 256-byte aligned, and may be NULL for host-only use (device calls then fail INVALID).
+ * The descriptors are copied.  *out is owned by the caller until jenga_pool_destroy. */
+int jenga_pool_create(void* device_base, int64_t pool_bytes, int64_t large_page_bytes,
+                      const jenga_kind_desc* kinds, int32_t n_kinds, jenga_pool** out);
+int jenga_pool_destroy(jenga_pool* pool);
+
+/* allocate() of Sec. 4.1 with the request-aware order of Sec. 4.3:
+ *   1. an unused small page of this kind inside a large page associated with `request`;
+ *   2. else a free large page: it becomes this kind's, all its small pages associated
+ *      with `request`;
+ *   3. else an unused small page of this kind associated with another request;
+ *   else JENGA_ERR_OOM.
+ * Ties: lowest-numbered large page, lowest slot in it.  The id returned is global for the
+ * kind: id = large_page * small_per_large + slot, so id * small_page_bytes is its byte
+ * offset from device_base (Sec. 4.1 last paragraph).  Its reference count starts at 1. */
+int jenga_alloc_small(jenga_pool* pool, int32_t kind, int64_t request, int32_t* out_small_id);
+/* One more reference to a live small page (prefix sharing). INVALID if it is unused. */
+int jenga_ref_small(jenga_pool* pool, int32_t kind, int32_t small_id);
+/* free(small_page_id) of Sec. 4.1: drop one reference; at zero the page is unused, and if
+ * every small page of its large page is unused the large page returns to level 1 at once
+ * and loses its kind and request.  INVALID on an unused page (double free). */
+int jenga_free_small(jenga_pool* pool, int32_t kind, int32_t small_id);
+
+int jenga_pool_get_info(const jenga_pool* pool, jenga_pool_info* out);
+int jenga_pool_kind_stats(const jenga_pool* pool, int32_t kind, jenga_kind_stats* out);
+/* Kind owning a large page (-1: free) and the request it is associated with (Sec. 4.3). */
+int jenga_large_page_owner(const jenga_pool* pool, int64_t large_page, int32_t* out_kind,
+                           int64_t* out_request);
+int jenga_small_refcount(const jenga_pool* pool, int32_t kind, int32_t small_id, int32_t* out);
+/* Byte offset from device_base of element 0 of (small page, layer, kv head, K or V, token). */
+int jenga_kv_offset(const jenga_pool* pool, int32_t kind, int32_t small_id, int32_t layer,
+                    int32_t kv_head, int32_t is_v, int32_t token_in_page, int64_t* out_bytes);
+
+/* ------------------------------------------- host: per-request page lists / block tables */
+
+/* Make kind `kind` of `request` hold tokens [0, new_len): logical pages are appended with
+ * jenga_alloc_small until ceil(new_len / tokens_per_page) exist; then, for WINDOW kinds,
+ * every resident page p with tokens_per_page * (p + 1) <= new_len - window is freed and its
+ * entry becomes -1 (only the window is needed, Sec. 5.1).  For OPAQUE kinds new_len counts
+ * pages.  On OOM the pages obtained so far are kept and the error returned. */
+int jenga_request_extend(jenga_pool* pool, int64_t request, int32_t kind, int64_t new_len);
+/* dst (which must have no pages of this kind) starts as a sharer of src's first n_pages
+ * logical pages: each resident one gets one more reference. */
+int jenga_request_share_prefix(jenga_pool* pool, int64_t src_request, int64_t dst_request,
+                               int32_t kind, int32_t n_pages);
+/* The request finished: drop its reference on every page of every kind, forget it. */
+int jenga_request_free(jenga_pool* pool, int64_t request);
+int jenga_request_num_pages(const jenga_pool* pool, int64_t request, int32_t kind, int32_t* out);
+/* Row of kind `kind`'s block table for `request`: row[p] = small id of logical page p, -1 if
+ * not resident; entries past the request's pages are -1.  row: host, `width` entries.
+ * INVALID if the request has more than `width` pages. */
+int jenga_request_block_table_row(const jenga_pool* pool, int64_t request, int32_t kind,
+                                  int32_t* row, int32_t width);
+
+/* ------------------------------------------------------------------------ device: kernels */
+
+/* Store the new token's K and V of one layer for every request of the batch ("store KV
+ * cache for each token", Sec. 2): for request b with L = seq_lens[b] > 0 the token at
+ * position L - 1 goes to page block_table[b][(L - 1) / T], row (L - 1) % T (address map
+ * above).  k_new, v_new: device, [batch][n_kv_heads][head_dim] in the kind's dtype, 16-byte
+ * aligned.  block_table: device int32 [batch][bt_stride]; seq_lens: device int32 [batch],
+ * lengths *after* this append.  Requests with L <= 0 or a negative table entry are skipped.
+ * Errors: INVALID for CROSS / OPAQUE kinds, bad layer, NULL pointers, batch < 0. */
+int jenga_kv_append(const jenga_pool* pool, int32_t kind, int32_t layer,
+                    const void* k_new, const void* v_new,
+                    const int32_t* block_table, int32_t bt_stride,
+                    const int32_t* seq_lens, int32_t batch, jenga_stream stream);
+
+/* Number of split-K partitions per (request, KV head) the decode kernels will use for these
+ * arguments, and the tokens per partition actually chosen.  pages_per_split = 0 lets the
+ * library choose from batch, heads and max_seq_len.  Returns the split count (>= 1) or a
+ * negative status. */
+int jenga_decode_num_splits(const jenga_pool* pool, int32_t kind, int32_t batch,
+                            int32_t max_seq_len, int32_t window, int32_t pages_per_split,
+                            int32_t* out_pages_per_split);
+/* Bytes of split-K workspace jenga_paged_decode needs for these arguments (> 0), or a
+ * negative status. */
+int64_t jenga_decode_workspace_bytes(const jenga_pool* pool, int32_t kind, int32_t n_q_heads,
+                                     int32_t batch, int32_t max_seq_len, int32_t window,
+                                     int32_t pages_per_split);
+
+/* Batched single-token decode attention of one layer through the kind's block table
+ * (kernel interface of Sec. 4.2).  For request b and query head h (KV head h / G,
+ * G = n_q_heads / n_kv_heads):
+ *     out[b][h][:] = sum_{t in Vis_b} softmax_t(scale * <q[b][h], K_t>) * V_t
+ * Vis_b = [max(0, L_b - window), L_b) if window > 0, else [0, L_b), L_b = seq_lens[b]
+ * (for CROSS kinds L_b is the encoder length).  fp32 accumulation; out is fp32
+ * [batch][n_q_heads][head_dim]; L_b <= 0 gives zeros.
+ *   q            device, [batch][n_q_heads][head_dim] in the kind's dtype, 16-byte aligned
+ *   block_table  device int32 [batch][bt_stride]; every page overlapping Vis_b must be
+ *                resident (>= 0); other entries are never read
+ *   seq_lens     device int32 [batch], each <= max_seq_len (larger ones are clamped)
+ *   max_seq_len  host upper bound of seq_lens; sizes the grid; bt_stride * T >= max_seq_len
+ *   window       0: none.  Pass the kind's window for WINDOW kinds.
+ *   pages_per_split  0: automatic; else pages of K/V per split-K partition
+ *   workspace    device, >= jenga_decode_workspace_bytes(...), 16-byte aligned, caller-owned;
+ *                holds per-partition (max, sum, accumulator) between the two kernels
+ * Runs the partial kernel and the split-K reduction on `stream`.
+ * Errors: INVALID, ALIGN, WORKSPACE, UNSUPPORTED (G not in {1,2,4,8}, head_dim), HIP. */
+int jenga_paged_decode(const jenga_pool* pool, int32_t kind, int32_t layer,
+                       const void* q, int32_t n_q_heads,
+                       const int32_t* block_table, int32_t bt_stride,
+                       const int32_t* seq_lens, int32_t batch, int32_t max_seq_len,
+                       int32_t window, float scale, int32_t pages_per_split,
+                       void* workspace, int64_t workspace_bytes,
+                       float* out, jenga_stream stream);
+/* The two kernels of jenga_paged_decode one at a time (same arguments, same checks):
+ * the partial kernel fills `workspace`; the reduction merges it into `out` by the
+ * log-sum-exp rule  m* = max m_i,  out = sum_i acc_i 2^(m_i - m*) / sum_i l_i 2^(m_i - m*). */
+int jenga_paged_decode_partial(const jenga_pool* pool, int32_t kind, int32_t layer,
+                               const void* q, int32_t n_q_heads,
+                               const int32_t* block_table, int32_t bt_stride,
+                               const int32_t* seq_lens, int32_t batch, int32_t max_seq_len,
+                               int32_t window, float scale, int32_t pages_per_split,
+                               void* workspace, int64_t workspace_bytes, jenga_stream stream);
+int jenga_splitk_reduce(const jenga_pool* pool, int32_t kind, int32_t n_q_heads,
+                        const int32_t* seq_lens, int32_t batch, int32_t max_seq_len,
+                        int32_t window, int32_t pages_per_split,
+                        const void* workspace, int64_t workspace_bytes,
+                        float* out, jenga_stream stream);
+
+/* Measurement aids (not on the hot path): a plain device copy and a plain device read of
+ * `bytes` (multiple of 16) with 16-byte accesses, used to find the achievable HBM rate and
+ * to calibrate profiler byte counters.  `sink`: device, >= 4 bytes. */
+int jenga_stream_copy(void* dst, const void* src, int64_t bytes, jenga_stream stream);
+int jenga_stream_read(const void* src, int64_t bytes, void* sink, jenga_stream stream);
+
+const char* jenga_strerror(int status);
+/* 0xMMmmpp */
+int jenga_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* JENGA_H */

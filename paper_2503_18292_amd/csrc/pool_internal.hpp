@@ -1,0 +1,54 @@
+// Internal layout of the host pool object, shared by the allocator (pool.cpp)
+// and the kernel launchers (kernels.hip).  Not part of the C ABI.
+#pragma once
+
+#include <cstdint>
+#include <set>
+#include <unordered_map>
+#include <vector>
+
+#include "jenga.h"
+
+namespace jenga {
+
+struct Kind {
+  jenga_kind_desc desc{};
+  int64_t small_bytes = 0;   // S_k
+  int64_t slice_bytes = 0;   // one layer's K+V for one page of tokens (0 for OPAQUE)
+  int64_t per_large = 0;     // r_k
+  int32_t elem_bytes = 0;
+  int32_t t_log2 = 0;
+
+  // level 2 state.  Bit `sid` of `used` is set while small page sid has references;
+  // `extra_refs` holds (count - 1) for pages with more than one reference.
+  std::vector<uint64_t> used;
+  std::unordered_map<int32_t, int32_t> extra_refs;
+  // large pages of this kind that still have an unused slot: all of them (step 3),
+  // and grouped by the request they are associated with (step 1).  Ordered, so the
+  // lowest-numbered one is *begin().
+  std::set<int64_t> with_room;
+  std::unordered_map<int64_t, std::set<int64_t>> with_room_by_request;
+  int64_t owned_large = 0;
+  int64_t used_small = 0;
+};
+
+struct RequestPages {
+  std::vector<std::vector<int32_t>> pages;   // [kind][logical page] -> small id or -1
+  std::vector<int64_t> first_resident;       // [kind] every page below it is already -1
+};
+
+}  // namespace jenga
+
+struct jenga_pool {
+  char* base = nullptr;
+  int64_t pool_bytes = 0;
+  int64_t large_bytes = 0;
+  int64_t n_large = 0;
+  std::vector<jenga::Kind> kinds;
+  // level 1 state
+  std::vector<int32_t> large_kind;        // -1: free
+  std::vector<int64_t> large_request;     // valid while large_kind >= 0
+  std::vector<int32_t> large_unused;      // unused slots left, valid while owned
+  std::set<int64_t> free_large;           // ordered: lowest-numbered first
+  std::unordered_map<int64_t, jenga::RequestPages> requests;
+};

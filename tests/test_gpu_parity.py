@@ -1,0 +1,335 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element.
+
+Every case prefills the pool with NaN bytes and scatters NaN into token rows outside the
+visible set, so each parity check is also a check that nothing outside the visible set is
+read into the result.  Tolerances are the ones stated for this build: max abs 1e-5 for
+fp32 K/V; for bf16 K/V max abs 2e-2 and relative (norm-wise) 1e-2.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle.attn import decode_attention_one, visible_range
+from workloads import configs, layout, scripts
+from workloads.configs import CROSS, FULL, OPAQUE, WINDOW, KindCfg, LengthDist, ModelCfg
+
+pytestmark = pytest.mark.gpu
+
+TOL_F32_ABS = 1e-5
+TOL_BF16_ABS = 2e-2
+TOL_BF16_REL = 1e-2
+
+
+def _runner(cfg, seed, **kw):
+    from paper_2503_18292_amd.runner import DecodeRunner
+    return DecodeRunner(cfg, seed, **kw)
+
+
+def prepare(r, poison=True):
+    """Host step, NaN-prefilled pool, seeded contexts scattered (masked rows NaN), inputs made."""
+    r.build_contexts()
+    r.host_step()
+    r.pool_u8.fill_(0xFF if poison else 0)
+    for k, layer in r.schedule:
+        kd = r.cfg.kinds[k]
+        for b in range(r.cfg.batch):
+            K, V = r.contiguous_kv(k, layer, b)
+            L = int(r.seq_lens_host[k][b])
+            n_cached = L - (0 if kd.type == CROSS else 1)
+            if poison:
+                lo, _ = visible_range(L, kd.window)
+                K, V = K.clone(), V.clone()
+                K[:, :lo] = float("nan")
+                V[:, :lo] = float("nan")
+            layout.scatter_request(r.pool_u8, kd, layer, r.tables_host[k][b].tolist(), K, V, n_cached)
+    r.make_inputs(new_token_from_seeded_kv=True)
+
+
+def check_against_oracle(r, label=""):
+    torch.cuda.synchronize()
+    worst = 0.0
+    for k, layer in r.schedule:
+        kd = r.cfg.kinds[k]
+        q = r.inputs[(k, layer)][0].cpu().double().numpy()
+        got = r.out[(k, layer)].cpu().double().numpy()
+        for b in range(r.cfg.batch):
+            K, V = r.contiguous_kv(k, layer, b)
+            want = decode_attention_one(q[b], K.double().numpy(), V.double().numpy(), r.scale(k), kd.window)
+            err = np.abs(got[b] - want)
+            assert np.isfinite(got[b]).all(), f"{label} kind {k} layer {layer} request {b}: non-finite output"
+            if kd.dtype == "f32":
+                assert err.max() <= TOL_F32_ABS, f"{label} kind {k} layer {layer} req {b}: {err.max()}"
+            else:
+                assert err.max() <= TOL_BF16_ABS, f"{label} kind {k} layer {layer} req {b}: {err.max()}"
+                rel = np.linalg.norm(got[b] - want) / max(np.linalg.norm(want), 1e-30)
+                assert rel <= TOL_BF16_REL, f"{label} kind {k} layer {layer} req {b}: rel {rel}"
+            worst = max(worst, float(err.max()))
+    return worst
+
+
+def check_append_landed(r):
+    """The appended token, read back through the harness's own address map, is bit-exact."""
+    for k, layer in r.schedule:
+        kd = r.cfg.kinds[k]
+        if kd.type == CROSS:
+            continue
+        for b in range(r.cfg.batch):
+            K, V = r.contiguous_kv(k, layer, b)
+            Kg, Vg = r.gather(k, layer, b)
+            bits = lambda t: t.contiguous().view(torch.uint8)
+            assert torch.equal(bits(Kg[:, -1]), bits(K[:, -1]))
+            assert torch.equal(bits(Vg[:, -1]), bits(V[:, -1]))
+            lo, hi = visible_range(K.shape[1], kd.window)
+            assert torch.equal(bits(Kg[:, lo:hi]), bits(K[:, lo:hi]))
+            assert torch.equal(bits(Vg[:, lo:hi]), bits(V[:, lo:hi]))
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+def test_tiny_config_exhaustive(seed):
+    print(f"[case] tiny seed={seed}", flush=True)
+    r = _runner(configs.tiny(), seed)
+    prepare(r)
+    r.device_step()
+    worst = check_against_oracle(r, f"tiny/{seed}")
+    check_append_landed(r)
+    print(f"  worst abs err {worst:.3e}", flush=True)
+    r.close()
+
+
+def custom_cfg(dtype, D, Hq, Hkv, typ, window=0, batch=3, lo=1, hi=700, n_layers=2, T=16, cross_len=0):
+    kind = KindCfg("k", typ, dtype, n_layers, Hq, Hkv, D, T, window=window)
+    other = KindCfg("pad", OPAQUE, "f32", 1, tokens_per_page=1, opaque_page_bytes=3 * kind.slice_bytes)
+    return ModelCfg(name=f"{dtype}-D{D}-G{Hq // Hkv}-{typ}", kinds=[kind, other], batch=batch,
+                    ctx=LengthDist("uniform", lo, hi), cross_len=cross_len, build_chunk=64, n_dummy=1,
+                    dummy_ctx=(1, 200))
+
+
+SHAPES = [(dt, D, G) for dt in ("bf16", "f32") for D in (64, 128, 256) for G in (1, 2, 4, 8)]
+
+
+@pytest.mark.parametrize("dtype,D,G", SHAPES)
+def test_all_built_shapes_full_attention(dtype, D, G):
+    print(f"[case] full {dtype} D={D} G={G}", flush=True)
+    cfg = custom_cfg(dtype, D, 2 * G, 2, FULL, hi=600)
+    r = _runner(cfg, 10 + D + G)
+    prepare(r)
+    r.device_step()
+    check_against_oracle(r, cfg.name)
+    check_append_landed(r)
+    r.close()
+
+
+@pytest.mark.parametrize("dtype,D,G,W", [("bf16", 256, 2, 100), ("bf16", 128, 4, 64), ("bf16", 64, 1, 33),
+                                         ("f32", 128, 2, 32), ("f32", 64, 4, 17), ("bf16", 128, 8, 1),
+                                         ("f32", 256, 1, 500), ("bf16", 256, 2, 16)])
+def test_sliding_window_shapes(dtype, D, G, W):
+    print(f"[case] window {dtype} D={D} G={G} W={W}", flush=True)
+    cfg = custom_cfg(dtype, D, 2 * G, 2, WINDOW, window=W, hi=400)
+    r = _runner(cfg, 77 + W)
+    prepare(r)
+    # slide-out really happened: no page wholly left of the window is resident
+    for b in range(cfg.batch):
+        L = int(r.seq_lens_host[0][b])
+        row = r.tables_host[0][b].tolist()
+        for p, sid in enumerate(row):
+            touches = p * 16 < L and (p + 1) * 16 > max(0, L - W)
+            assert (sid >= 0) == touches
+    r.device_step()
+    check_against_oracle(r, cfg.name)
+    r.close()
+
+
+@pytest.mark.parametrize("Lx", [1, 15, 16, 17, 404, 1601])
+def test_cross_attention_ragged_encoder_length(Lx):
+    print(f"[case] cross Lx={Lx}", flush=True)
+    cfg = custom_cfg("bf16", 128, 8, 2, CROSS, cross_len=Lx, batch=2)
+    r = _runner(cfg, 5)
+    prepare(r)
+    r.device_step()
+    check_against_oracle(r, cfg.name)
+    r.close()
+
+
+@pytest.mark.parametrize("ctx", [[0, 0, 0], [15, 16, 17], [127, 128, 255], [0, 1023, 31]])
+def test_edge_lengths(ctx):
+    """L = 1 (a single token returns its value row), page and tile boundaries."""
+    print(f"[case] edge ctx={ctx}", flush=True)
+    for dtype, D in (("bf16", 256), ("f32", 64), ("bf16", 128)):
+        cfg = custom_cfg(dtype, D, 4, 2, FULL)
+        r = _runner(cfg, 3, ctx=np.array(ctx))
+        prepare(r)
+        r.device_step()
+        check_against_oracle(r, cfg.name)
+        for b, c in enumerate(ctx):
+            if c == 0:      # one visible token: softmax weight exactly 1
+                for k, layer in r.schedule:
+                    V = r.contiguous_kv(k, layer, b)[1].float()
+                    got = r.out[(k, layer)][b].cpu()
+                    for h in range(4):
+                        assert torch.equal(got[h], V[h // 2, 0])
+        r.close()
+
+
+def test_empty_batch_entries_give_zeros():
+    cfg = custom_cfg("bf16", 128, 4, 2, FULL)
+    r = _runner(cfg, 4, ctx=np.array([40, 9, 100]))
+    prepare(r)
+    lens = r.seq_lens[0].clone()
+    lens[1] = 0
+    r.seq_lens[0] = lens
+    for key in r.out:
+        r.out[key].fill_(7.0)
+    r.device_step()
+    torch.cuda.synchronize()
+    for k, layer in r.schedule:
+        assert torch.equal(r.out[(k, layer)][1].cpu(), torch.zeros(4, 128))
+    r.seq_lens_host[0][1] = 0
+    r.close()
+
+
+@pytest.mark.parametrize("dtype,D,G", [("bf16", 256, 2), ("bf16", 128, 4), ("f32", 64, 2)])
+def test_split_k_choices_agree(dtype, D, G):
+    """Any partition size gives the oracle's result; different sizes agree to rounding."""
+    print(f"[case] split-k {dtype} D={D} G={G}", flush=True)
+    outs = []
+    for pps in (0, 4, 8, 64, 256):
+        cfg = custom_cfg(dtype, D, 2 * G, 2, FULL, lo=900, hi=3000, n_layers=1)
+        r = _runner(cfg, 21, pages_per_split=pps)
+        prepare(r)
+        r.device_step()
+        check_against_oracle(r, f"{cfg.name}/pps{pps}")
+        outs.append(r.out[(0, 0)].cpu().clone())
+        r.close()
+    for o in outs[1:]:
+        assert (o - outs[0]).abs().max() <= (2e-6 if dtype == "f32" else 2e-5)
+
+
+def test_result_does_not_depend_on_physical_placement():
+    """Same tokens in different physical pages: bit-identical output."""
+    cfg = custom_cfg("bf16", 256, 4, 2, FULL, lo=300, hi=900, n_layers=2)
+    ctx = scripts.sample_ctx(cfg, 9)
+    outs, tabs = [], []
+    for script_seed in (100, 200):
+        r = _runner(cfg, 9, ctx=ctx, script_seed=script_seed)
+        prepare(r)
+        r.device_step()
+        torch.cuda.synchronize()
+        outs.append({key: v.cpu().clone() for key, v in r.out.items()})
+        tabs.append(r.tables_host[0].clone())
+        r.close()
+    assert not torch.equal(tabs[0], tabs[1]), "placements should differ"
+    for key in outs[0]:
+        assert torch.equal(outs[0][key], outs[1][key])
+
+
+def test_partial_plus_reduce_equals_fused_entry_point():
+    cfg = custom_cfg("bf16", 128, 8, 2, WINDOW, window=200, lo=100, hi=1500, n_layers=1)
+    r = _runner(cfg, 31, pages_per_split=4)
+    prepare(r)
+    r.run_layer(0, 0)
+    torch.cuda.synchronize()
+    fused = r.out[(0, 0)].cpu().clone()
+    r.out[(0, 0)].zero_()
+    r.run_layer(0, 0, split=True)
+    torch.cuda.synchronize()
+    assert torch.equal(fused, r.out[(0, 0)].cpu())
+    r.close()
+
+
+def test_opaque_pages_interleaved_and_untouched():
+    """Jamba-like pool: state pages sit between KV pages and no kernel writes them."""
+    cfg = configs.jamba_like()
+    cfg.batch = 6
+    for kd in cfg.kinds:
+        if kd.type == OPAQUE:     # smaller state pages keep the test pool small; ratios stay uneven
+            kd.n_layers, kd.opaque_page_bytes = 1, 7 * cfg.kinds[0].small_page_bytes
+    cfg.ctx = LengthDist("lognormal", 128, 2000, median=400.0, sigma=1.0)
+    cfg.build_chunk = 64
+    r = _runner(cfg, 2)
+    prepare(r)
+    sentinel = 0x5A
+    state_ids = [r.pool.request_block_table_row(req, 1, 1)[0] for req in r.requests]
+    S = cfg.kinds[1].small_page_bytes
+    for sid in state_ids:
+        r.pool_u8[sid * S:(sid + 1) * S] = sentinel
+    owners = [r.pool.large_page_owner(i)[0] for i in range(r.n_large)]
+    used = [o for o in owners if o >= 0]
+    assert any(a != b for a, b in zip(used, used[1:])), "kinds should interleave in the pool"
+    r.device_step()
+    check_against_oracle(r, "jamba-small")
+    for sid in state_ids:
+        assert bool((r.pool_u8[sid * S:(sid + 1) * S] == sentinel).all())
+    r.close()
+
+
+def test_prefix_sharing_reads_shared_pages():
+    cfg = configs.long_5to1()
+    cfg.batch = 8
+    cfg.share_tokens, cfg.share_fraction = 256, 0.5
+    cfg.ctx = LengthDist("uniform", 256, 1500)
+    for kd in cfg.kinds:
+        kd.n_layers = 1
+        kd.window = 128 if kd.type == WINDOW else 0
+    cfg.build_chunk = 128
+    r = _runner(cfg, 12)
+    r.build_contexts()
+    r.host_step()
+    group = scripts.sharers(cfg, r.ctx, 12)
+    assert len(group) >= 2
+    # sharers hold the same physical pages for the shared prefix of the full kind
+    lead_row = r.tables_host[1][group[0]][:16]
+    for b in group[1:]:
+        assert torch.equal(r.tables_host[1][b][:16], lead_row)
+    # values: the sharers' first 256 tokens must be the leader's, since the pages are the same
+    orig = r.contiguous_kv
+
+    def shared_kv(k, layer, b):
+        K, V = orig(k, layer, b)
+        if k == 1 and b in group[1:]:
+            Kl, Vl = orig(k, layer, group[0])
+            K, V = K.clone(), V.clone()
+            K[:, :256], V[:, :256] = Kl[:, :256], Vl[:, :256]
+        return K, V
+
+    r.contiguous_kv = shared_kv
+    r._built = True
+    r.pool_u8.fill_(0xFF)
+    for k, layer in r.schedule:
+        kd = cfg.kinds[k]
+        for b in range(cfg.batch):
+            K, V = r.contiguous_kv(k, layer, b)
+            layout.scatter_request(r.pool_u8, kd, layer, r.tables_host[k][b].tolist(), K, V,
+                                   int(r.seq_lens_host[k][b]) - 1)
+    r.make_inputs(new_token_from_seeded_kv=True)
+    r.device_step()
+    check_against_oracle(r, "prefix-sharing")
+    r.close()
+
+
+def test_device_entry_points_reject_bad_arguments():
+    import paper_2503_18292_amd as J
+    cfg = custom_cfg("bf16", 128, 4, 2, FULL)
+    r = _runner(cfg, 1)
+    prepare(r)
+    q, k_new, v_new = r.inputs[(0, 0)]
+    with pytest.raises(J.JengaError) as e:      # workspace too small
+        r.pool.paged_decode(0, 0, q, r.tables[0], r.seq_lens[0], r.max_len[0], 0, 0.1,
+                            r.workspace[0][:4], r.out[(0, 0)])
+    assert e.value.status == -4
+    with pytest.raises(J.JengaError):           # block table narrower than max_seq_len
+        r.pool.paged_decode(0, 0, q, r.tables[0][:, :1].contiguous(), r.seq_lens[0], 4096, 0, 0.1,
+                            r.workspace[0], r.out[(0, 0)])
+    with pytest.raises(J.JengaError):           # layer out of range
+        r.pool.kv_append(0, 99, k_new, v_new, r.tables[0], r.seq_lens[0])
+    with pytest.raises(J.JengaError):           # OPAQUE kind has no kernels
+        r.pool.kv_append(1, 0, k_new, v_new, r.tables[0], r.seq_lens[0])
+    with pytest.raises(J.JengaError) as e:      # misaligned q
+        base = torch.empty(q.numel() + 8, dtype=q.dtype, device=q.device)
+        q_mis = base[1:1 + q.numel()].view(q.shape)          # 2 bytes off a 16-byte boundary
+        r.pool.paged_decode(0, 0, q_mis, r.tables[0], r.seq_lens[0], r.max_len[0],
+                            0, 0.1, r.workspace[0], r.out[(0, 0)])
+    assert e.value.status == -3
+    torch.cuda.synchronize()
+    r.close()

@@ -1,0 +1,224 @@
+"""Host half of the library against the allocator oracle: ids, block tables and state, bit for bit.
+
+Runs without a GPU: the pool is created over a NULL device base and only host entry points
+are called.  Also checks that the shared library exports every function include/jenga.h declares.
+"""
+import os
+import re
+import subprocess
+
+import numpy as np
+import pytest
+
+from oracle.alloc import InvalidOp, OraclePool, OutOfPages, lcm_bytes
+from workloads import configs, scripts
+
+import paper_2503_18292_amd as J
+from paper_2503_18292_amd import _lib
+from paper_2503_18292_amd.api import make_kind
+
+from helpers import (kind_descs, large_pages_for, library_table, make_library, make_oracle,
+                     oracle_table, table_width)
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_every_declared_symbol_is_exported_and_bound():
+    header = open(os.path.join(ROOT, "include", "jenga.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(jenga_[a-z0-9_]+)\s*\(", header))
+    assert len(declared) >= 20
+    out = subprocess.run(["nm", "-D", "--defined-only", _lib.LIB_PATH], capture_output=True, text=True,
+                         check=True).stdout
+    exported = set(re.findall(r"\sT\s+(jenga_[a-z0-9_]+)", out))
+    assert declared <= exported, declared - exported
+    assert declared == set(_lib.SIGNATURES), declared ^ set(_lib.SIGNATURES)
+    lib = _lib.load()
+    for name in declared:
+        assert getattr(lib, name) is not None
+    assert J.version() == 0x000100
+
+
+def test_lcm_matches_paper_examples():
+    K = lambda s: make_kind(J.OPAQUE, small_page_bytes=s)
+    assert J.lcm_page_bytes([K(2048), K(3072)]) == 6144                 # Sec. 1
+    assert J.lcm_page_bytes([K(256), K(384)]) == 768                    # Sec. 4.1 figure
+    for name, fn in configs.ALL.items():
+        cfg = fn()
+        assert J.lcm_page_bytes(kind_descs(cfg)) == lcm_bytes([k.small_page_bytes for k in cfg.kinds])
+
+
+def test_two_level_overview_figure_through_the_abi():
+    K = lambda s: make_kind(J.OPAQUE, small_page_bytes=s)
+    pool = J.Pool(None, 8 * 768, [K(256), K(384)])
+    ids = {0: [], 1: []}
+    for k in [0, 1, 0, 0, 1, 0]:
+        ids[k].append(pool.alloc_small(k, 7))
+    assert ids[0] == [0, 1, 2, 6] and ids[1] == [2, 3]
+    assert pool.large_page_owner(1) == (1, 7)
+    assert pool.kind_stats(0).small_per_large == 3 and pool.kind_stats(1).small_per_large == 2
+
+
+@pytest.mark.parametrize("seed,sizes,n_large,n_ops", [
+    (1, [256, 384], 12, 3000), (2, [16384, 32768], 16, 3000), (3, [2048, 3072, 6144], 10, 3000),
+    (4, [512 * 1024, 2048 * 1024], 6, 2000), (5, [4096, 28672 * 8], 5, 3000), (6, [64, 6400], 40, 6000)])
+def test_lowlevel_traces_match_oracle_bit_for_bit(seed, sizes, n_large, n_ops):
+    L = lcm_bytes(sizes)
+    ora = OraclePool(n_large * L, sizes)
+    lib = J.Pool(None, n_large * L, [make_kind(J.OPAQUE, small_page_bytes=s) for s in sizes])
+    assert lib.get_info().n_large_pages == ora.n_large
+    ops = scripts.lowlevel_trace(len(sizes), 7, n_ops, seed)
+    h2, refs = {}, {}
+    n_oom = 0
+    for i, op in enumerate(ops):
+        if op[0] == "alloc":
+            _, h, k, req = op
+            try:
+                want = ora.alloc(k, req)
+            except OutOfPages:
+                want = None
+            if want is None:
+                with pytest.raises(J.JengaError) as e:
+                    lib.alloc_small(k, req)
+                assert e.value.status == -2
+                n_oom += 1
+                refs[h] = 0
+            else:
+                assert lib.alloc_small(k, req) == want, f"op {i}"
+                h2[h] = (k, want)
+                refs[h] = 1
+        elif op[0] == "ref" and refs.get(op[1], 0) > 0:
+            ora.ref(*h2[op[1]]); lib.ref_small(*h2[op[1]]); refs[op[1]] += 1
+        elif op[0] == "unref" and refs.get(op[1], 0) > 0:
+            ora.free(*h2[op[1]]); lib.free_small(*h2[op[1]]); refs[op[1]] -= 1
+        if i % 97 == 0 or i == len(ops) - 1:
+            assert lib.get_info().free_large_pages == ora.free_large()
+            for k in range(len(sizes)):
+                st = lib.kind_stats(k)
+                assert st.owned_large_pages == ora.owned_large(k)
+                assert st.used_small_pages == ora.used_small(k)
+                assert st.unused_small_pages == ora.unused_small_in_owned(k)
+            for large in range(ora.n_large):
+                ok, orq = ora.large_owner(large)
+                lk, lrq = lib.large_page_owner(large)
+                assert lk == ok and (ok < 0 or lrq == orq)
+            for k in range(len(sizes)):
+                for sid in range(0, ora.refcount[k].size, max(1, ora.refcount[k].size // 64)):
+                    assert lib.small_refcount(k, sid) == ora.refcount[k][sid]
+    assert lib.get_info().free_large_pages == lib.get_info().n_large_pages
+    assert n_oom > 0 or n_large > 20
+
+
+@pytest.mark.parametrize("name,seed", [("tiny", 0), ("tiny", 1), ("tiny", 2), ("llama32_vision_11b", 3),
+                                       ("jamba_like", 4), ("gemma2_9b", 5), ("long_5to1", 6)])
+def test_block_tables_match_oracle_bit_for_bit(name, seed):
+    cfg = configs.ALL[name]()
+    if name not in ("tiny",):
+        cfg.batch = {"llama32_vision_11b": 6, "jamba_like": 12, "gemma2_9b": 5, "long_5to1": 12}[name]
+    ctx = scripts.sample_ctx(cfg, seed)
+    if name == "long_5to1":
+        ctx = np.minimum(ctx, 20000)
+    n_large = large_pages_for(cfg, ctx)
+    ora_pool, ora = make_oracle(cfg, n_large)
+    lib = make_library(cfg, n_large)
+    for script in (scripts.build_script(cfg, ctx, seed), scripts.step_script(cfg, ctx)):
+        scripts.run_script(script, ora)
+        scripts.run_script(script, lib)
+        for k in range(len(cfg.kinds)):
+            w = table_width(cfg, k, ctx)
+            assert np.array_equal(oracle_table(ora, cfg, k, w), library_table(lib, cfg, k, w))
+            st = lib.kind_stats(k)
+            assert st.used_small_pages == ora_pool.used_small(k)
+            assert st.owned_large_pages == ora_pool.owned_large(k)
+        assert lib.get_info().free_large_pages == ora_pool.free_large()
+    if name == "long_5to1":
+        group = scripts.sharers(cfg, ctx, seed)
+        assert len(group) >= 2
+        full = 1
+        w = table_width(cfg, full, ctx)
+        shared = lib.request_block_table_row(scripts.request_id(group[0]), full, w)[:256]
+        for b in group[1:]:
+            assert lib.request_block_table_row(scripts.request_id(b), full, w)[:256] == shared
+        assert lib.small_refcount(full, shared[0]) == len(group)
+    fin = scripts.finish_script(cfg, seed)
+    scripts.run_script(fin, ora)
+    scripts.run_script(fin, lib)
+    assert lib.get_info().free_large_pages == lib.get_info().n_large_pages == ora_pool.n_large
+    for k in range(len(cfg.kinds)):
+        assert lib.kind_stats(k).used_small_pages == 0
+
+
+def test_kv_offset_matches_the_harness_address_map():
+    import torch
+    from workloads import layout
+    cfg = configs.tiny()
+    lib = make_library(cfg, 8)
+    for ki, kind in enumerate(cfg.kinds):
+        pool_u8 = torch.zeros(8 * 32768, dtype=torch.uint8)
+        for (sid, layer, head, is_v, tok) in [(0, 0, 0, 0, 0), (1, 0, 1, 1, 5), (3, 0, 1, 0, 15), (2, 0, 0, 1, 7)]:
+            if sid >= 8 * 32768 // kind.small_page_bytes:
+                continue
+            off = lib.kv_offset(ki, sid, layer, head, is_v, tok)
+            pool_u8.zero_()
+            view = layout._slice_view(pool_u8, kind, sid, layer)
+            view[head, is_v, tok, 0] = 1.0
+            nz = torch.nonzero(pool_u8).flatten()
+            assert int(nz[0]) // 4 * 4 == off
+
+
+def test_error_paths():
+    K = lambda s: make_kind(J.OPAQUE, small_page_bytes=s)
+    with pytest.raises(J.JengaError) as e:
+        J.Pool(None, 4096, [K(256), K(384)], large_page_bytes=1000)      # not a common multiple
+    assert e.value.status == -1
+    with pytest.raises(J.JengaError) as e:
+        J.Pool(None, 4096, [K(250)])                                      # not 16-byte aligned
+    assert e.value.status == -3
+    with pytest.raises(J.JengaError) as e:
+        J.Pool(None, 4096, [make_kind(J.FULL, J.BF16, 1, 2, 96, 16)])    # head_dim outside the built set
+    assert e.value.status == -6
+    with pytest.raises(J.JengaError):
+        J.Pool(None, 4096, [make_kind(J.WINDOW, J.BF16, 1, 2, 64, 16, window=0)])
+    with pytest.raises(J.JengaError):
+        J.Pool(128, 4096, [K(256)])                                       # base not 256-byte aligned
+    pool = J.Pool(None, 2 * 768, [K(256), K(384)])
+    a = pool.alloc_small(0, 1)
+    pool.free_small(0, a)
+    for bad in (lambda: pool.free_small(0, a), lambda: pool.ref_small(0, a),
+                lambda: pool.alloc_small(2, 1), lambda: pool.free_small(0, 10 ** 6),
+                lambda: pool.request_free(12345), lambda: pool.request_extend(1, 0, -1),
+                lambda: pool.large_page_owner(99)):
+        with pytest.raises(J.JengaError) as e:
+            bad()
+        assert e.value.status == -1
+    # exhaustion is reported, not fatal, and the pool stays consistent
+    got = [pool.alloc_small(1, 5) for _ in range(4)]
+    with pytest.raises(J.JengaError) as e:
+        pool.alloc_small(1, 5)
+    assert e.value.status == -2
+    for s in got:
+        pool.free_small(1, s)
+    assert pool.get_info().free_large_pages == 2
+    # device entry points refuse a pool without device memory, and non-attention kinds
+    with pytest.raises(J.JengaError):
+        pool._lib.jenga_kv_append  # symbol exists
+        J.api._check(pool._lib.jenga_kv_append(pool._h, 0, 0, 16, 16, 16, 1, 16, 1, None), "append")
+    assert pool._lib.jenga_decode_workspace_bytes(pool._h, 0, 4, 1, 16, 0, 0) == -1
+
+
+def test_split_geometry_and_workspace_queries():
+    cfg = configs.gemma2_9b()
+    lib = make_library(cfg, 4)
+    n, pps = lib.decode_num_splits(0, 64, 8193)
+    assert n == -(-513 // pps) and pps >= 1
+    ws = lib.decode_workspace_bytes(0, 16, 64, 8193)
+    assert ws == 64 * 16 * n * (256 + 2) * 4
+    nw, ppsw = lib.decode_num_splits(1, 64, 8193, window=4096)
+    assert nw * ppsw >= 4096 // 16 + 1 and nw < n
+    n1, pps1 = lib.decode_num_splits(0, 64, 8193, pages_per_split=32)
+    assert pps1 == 32 and n1 == -(-513 // 32)
+    with pytest.raises(J.JengaError):
+        lib.decode_num_splits(0, 64, 8193, pages_per_split=100000)
+    with pytest.raises(J.JengaError) as e:
+        lib.decode_workspace_bytes(0, 24, 64, 8193)      # 24 query heads over 8 KV heads: G = 3
+    assert e.value.status == -6

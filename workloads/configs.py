@@ -146,3 +146,22 @@ ALL = {
     "jamba_like": jamba_like,
     "long_5to1": long_5to1,
 }
+
+
+def layer_schedule(cfg: ModelCfg):
+    """Model order of the attention layers as (kind index, layer within kind).
+
+    Kinds are interleaved in proportion to their layer counts (alternating for the
+    Gemma-2 shape, every fifth layer cross-attention for the Llama-3.2-Vision shape).
+    """
+    att = [(i, k) for i, k in enumerate(cfg.kinds) if k.type != OPAQUE]
+    total = sum(k.n_layers for _, k in att)
+    done = {i: 0 for i, _ in att}
+    out = []
+    for step in range(total):
+        # pick the kind that is furthest behind its share
+        i, k = min(att, key=lambda ik: ((done[ik[0]] + 1) / ik[1].n_layers, -ik[1].n_layers)
+                   if done[ik[0]] < ik[1].n_layers else (float("inf"), 0))
+        out.append((i, done[i]))
+        done[i] += 1
+    return out
