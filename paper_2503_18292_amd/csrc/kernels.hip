@@ -111,12 +111,16 @@ __device__ __forceinline__ float dot16(const u32x4& k, const u32x4& q) {
     s = fmaf(__uint_as_float(k.w), __uint_as_float(q.w), s);
     return s;
   } else {
-    // v_dot2_f32_bf16: two bf16 products accumulated in fp32 per instruction
+    // v_dot2_f32_bf16: two bf16 products accumulated in fp32 per instruction.  The words are
+    // copied to scalars first: a bit cast applied directly to a vector element read the
+    // first element every time with this compiler.
+    const unsigned kw[4] = {k.x, k.y, k.z, k.w};
+    const unsigned qw[4] = {q.x, q.y, q.z, q.w};
     float s = 0.f;
-    s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, k.x), __builtin_bit_cast(bf16x2_t, q.x), s, false);
-    s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, k.y), __builtin_bit_cast(bf16x2_t, q.y), s, false);
-    s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, k.z), __builtin_bit_cast(bf16x2_t, q.z), s, false);
-    s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, k.w), __builtin_bit_cast(bf16x2_t, q.w), s, false);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, kw[i]),
+                                          __builtin_bit_cast(bf16x2_t, qw[i]), s, false);
     return s;
   }
 }
