@@ -1,0 +1,201 @@
+#!/usr/bin/env python3
+"""Benchmark: decode steps of a synthetic heterogeneous-KV workload on one MI355X.
+
+A step is the whole hot path once: the host allocator makes room for every request's
+new token (two-level LCM pool, request-aware placement, window slide-out), block tables
+and lengths go to the device, and for each attention layer in model order the new K/V is
+appended and paged decode attention (partial + split-K reduce) runs through that layer
+type's block table.  Inputs are resident in HBM before the timed region.
+
+Prints ONE JSON line: metric = K/V bytes read per second over whole steps, plus
+`roofline` for the dominant kernel (timed with events on the launch stream inside the
+timed region) and `cpu_baseline` (the CPU oracle timed on a bounded sample).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="gemma2_9b",
+                    choices=["tiny", "gemma2_9b", "llama32_vision_11b", "jamba_like", "long_5to1"])
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--pages-per-split", type=int, default=0, help="0: library's choice")
+    ap.add_argument("--no-kernel-events", action="store_true",
+                    help="do not bracket the decode kernel with events (roofline.achieved becomes null)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle timing")
+    return ap.parse_args()
+
+
+def cpu_baseline(runner, budget_s: float):
+    """The fp64 oracle on the host cores, on (request, layer) slices gathered from the pool."""
+    import numpy as np
+    import torch
+    from oracle.attn import decode_attention_one
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = 1
+    torch.cuda.synchronize()
+    t_used, nbytes, n_units, toks = 0.0, 0, 0, 0
+    per_kind = {}
+    for k in runner.attn_kinds:
+        kd = runner.cfg.kinds[k]
+        layer = 0
+        q = runner.inputs[(k, layer)][0].cpu().double().numpy()
+        t_kind, b_kind, n_kind = 0.0, 0, 0
+        for b in range(runner.cfg.batch):
+            if t_used >= budget_s * (runner.attn_kinds.index(k) + 1) / len(runner.attn_kinds):
+                break
+            K, V = runner.gather(k, layer, b)
+            Kd, Vd = K.double().numpy(), V.double().numpy()
+            vis = int(runner.visible_tokens(k)[b])
+            Kd[:, :Kd.shape[1] - vis] = 0.0      # rows outside the window are never read by the oracle
+            Vd[:, :Vd.shape[1] - vis] = 0.0
+            t0 = time.perf_counter()
+            decode_attention_one(q[b], Kd, Vd, runner.scale(k), kd.window)
+            dt = time.perf_counter() - t0
+            t_used += dt
+            t_kind += dt
+            b_kind += vis * kd.bytes_per_token_per_layer
+            n_kind += 1
+        per_kind[k] = (t_kind, b_kind, n_kind)
+        nbytes += b_kind
+        n_units += n_kind
+    gbs = nbytes / t_used / 1e9 if t_used > 0 else 0.0
+    # scale the sample to a whole step: every layer of a kind has the same shapes
+    step_s = 0.0
+    for k, (t_kind, b_kind, n_kind) in per_kind.items():
+        if b_kind:
+            step_s += t_kind * runner.kv_bytes_layer(k) / b_kind * runner.cfg.kinds[k].n_layers
+    return {
+        "value": round(gbs, 4), "unit": "GB/s", "cores": int(threads), "kind": "oracle",
+        "sample": f"{n_units} (request, layer) slices: layer 0 of each attention kind, requests in batch "
+                  f"order until {budget_s:.0f} s of oracle time; fp64 numpy; scaled to a whole step by "
+                  f"layer count: {step_s:.1f} s/step = {runner.cfg.batch / step_s if step_s else 0:.3f} tokens/s",
+        "seconds": round(t_used, 2),
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "run it with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2503_18292_amd import _lib
+    from paper_2503_18292_amd.runner import DecodeRunner
+    from workloads import configs
+
+    _lib.load()     # no library, no benchmark: there is no other path
+    cfg = configs.ALL[args.workload]()
+    total_steps = args.steps + args.warmup
+    t_setup = time.perf_counter()
+    r = DecodeRunner(cfg, args.seed, pages_per_split=args.pages_per_split, step_budget=total_steps + 2)
+    r.build_contexts()
+    r.host_step()
+    r.fill_pool_random()
+    r.make_inputs(new_token_from_seeded_kv=False)
+    torch.cuda.synchronize()
+    print(f"[bench] {cfg.name}: pool {r.pool_u8.numel() / 2**30:.1f} GiB in {r.n_large} large pages of "
+          f"{r.large_bytes // 1024} KiB; batch {cfg.batch}; ctx {int(r.ctx.min())}..{int(r.ctx.max())}; "
+          f"setup {time.perf_counter() - t_setup:.1f} s", file=sys.stderr, flush=True)
+
+    def one_step(events=None):
+        r.advance()
+        r.device_step(events)
+
+    # step 0 of the runner was the host_step above; run its device part as the first warmup
+    r.device_step()
+    for _ in range(max(0, args.warmup - 1)):
+        one_step()
+    torch.cuda.synchronize()
+
+    use_events = not args.no_kernel_events
+    ev = []
+    if use_events:
+        for _ in range(args.steps):
+            ev.append({key: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+                       for key in r.schedule})
+    step_bytes = []
+    layer_bytes = []
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        one_step(ev[i] if use_events else None)
+        step_bytes.append(r.kv_bytes_step())
+        layer_bytes.append({k: r.kv_bytes_layer(k) for k in r.attn_kinds})
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    elapsed = t1 - t0
+    ms_per_step = elapsed / args.steps * 1e3
+    total_bytes = float(sum(step_bytes))
+    gbs = total_bytes / elapsed / 1e9
+    tokens_per_s = cfg.batch * args.steps / elapsed
+
+    roof = {"bound": "hbm", "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": None,
+            "traffic": None, "kernel": "decode_partial_kernel"}
+    if use_events:
+        k_ms, k_bytes, n_launch = 0.0, 0.0, 0
+        per_kind_ms = {k: 0.0 for k in r.attn_kinds}
+        per_kind_bytes = {k: 0.0 for k in r.attn_kinds}
+        for i in range(args.steps):
+            for (k, layer), (e0, e1) in ev[i].items():
+                ms = e0.elapsed_time(e1)
+                k_ms += ms
+                k_bytes += layer_bytes[i][k]
+                per_kind_ms[k] += ms
+                per_kind_bytes[k] += layer_bytes[i][k]
+                n_launch += 1
+        achieved = k_bytes / (k_ms * 1e-3) / 1e9
+        roof.update({
+            "achieved": round(achieved, 1), "frac": round(achieved / HBM_PEAK_GBS, 4),
+            "launches": n_launch, "avg_launch_us": round(k_ms / n_launch * 1e3, 2),
+            "algorithmic_bytes_per_launch": round(k_bytes / n_launch),
+            "per_kind_GBps": {cfg.kinds[k].name: round(per_kind_bytes[k] / (per_kind_ms[k] * 1e-3) / 1e9, 1)
+                              for k in r.attn_kinds},
+        })
+
+    line = {
+        "metric": "paged-decode KV read GB/s (% HBM peak) and decode tokens/s, 1 MI355X",
+        "value": round(gbs, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": cfg.kinds[r.attn_kinds[0]].dtype,
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "batch": cfg.batch, "kv_storage": cfg.kinds[r.attn_kinds[0]].dtype,
+                   "accumulate": "f32",
+                   "ctx_tokens": [int(r.ctx.min()), int(r.ctx.max())],
+                   "attention_layers": len(r.schedule), "kv_bytes_per_step": int(step_bytes[-1]),
+                   "pool_GiB": round(r.pool_u8.numel() / 2**30, 1)},
+        "tokens_per_s": round(tokens_per_s, 1),
+        "pct_hbm_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2),
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(r, args.cpu_seconds)
+    print(json.dumps(line), flush=True)
+    r.close()
+
+
+if __name__ == "__main__":
+    main()

@@ -163,6 +163,15 @@ int jenga_request_num_pages(const jenga_pool* pool, int64_t request, int32_t kin
 int jenga_request_block_table_row(const jenga_pool* pool, int64_t request, int32_t kind,
                                   int32_t* row, int32_t width);
 
+/* Batched forms for a decode step over n requests (host arrays of n entries):
+ * jenga_requests_extend == jenga_request_extend(requests[i], kind, new_lens[i]) for i in order,
+ * stopping at the first error; jenga_block_table_fill writes row i of a host table
+ * [n][width] as jenga_request_block_table_row does. */
+int jenga_requests_extend(jenga_pool* pool, int32_t kind, const int64_t* requests,
+                          const int64_t* new_lens, int32_t n);
+int jenga_block_table_fill(const jenga_pool* pool, int32_t kind, const int64_t* requests, int32_t n,
+                           int32_t* table, int32_t width);
+
 /* ------------------------------------------------------------------------ device: kernels */
 
 /* Store the new token's K and V of one layer for every request of the batch ("store KV

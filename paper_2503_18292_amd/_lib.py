@@ -49,6 +49,8 @@ SIGNATURES = {
     "jenga_request_free": (C.c_int, [c_vp, c_i64]),
     "jenga_request_num_pages": (C.c_int, [c_vp, c_i64, c_i32, p_i32]),
     "jenga_request_block_table_row": (C.c_int, [c_vp, c_i64, c_i32, p_i32, c_i32]),
+    "jenga_requests_extend": (C.c_int, [c_vp, c_i32, c_vp, c_vp, c_i32]),
+    "jenga_block_table_fill": (C.c_int, [c_vp, c_i32, c_vp, c_i32, c_vp, c_i32]),
     "jenga_kv_append": (C.c_int, [c_vp, c_i32, c_i32, c_vp, c_vp, c_vp, c_i32, c_vp, c_i32, c_vp]),
     "jenga_decode_num_splits": (C.c_int, [c_vp, c_i32, c_i32, c_i32, c_i32, c_i32, p_i32]),
     "jenga_decode_workspace_bytes": (c_i64, [c_vp, c_i32, c_i32, c_i32, c_i32, c_i32, c_i32]),

@@ -177,6 +177,17 @@ class Pool:
                 "jenga_request_block_table_row")
         return torch.from_numpy(tab)
 
+    def requests_extend(self, kind: int, requests, new_lens) -> None:
+        """requests, new_lens: contiguous int64 numpy arrays of equal length."""
+        _check(self._lib.jenga_requests_extend(self._h, kind, requests.ctypes.data, new_lens.ctypes.data,
+                                               len(requests)), "jenga_requests_extend")
+
+    def block_table_fill(self, kind: int, requests, table) -> None:
+        """requests: int64 numpy array [n]; table: host int32 torch tensor [n, width], filled in place."""
+        _check(self._lib.jenga_block_table_fill(self._h, kind, requests.ctypes.data, len(requests),
+                                                table.data_ptr(), table.shape[1]),
+               "jenga_block_table_fill")
+
     # aliases so a script runner can drive the library and the oracle alike
     extend = request_extend
     share_prefix = request_share_prefix

@@ -384,6 +384,27 @@ int jenga_request_block_table_row(const jenga_pool* pool, int64_t request, int32
   return JENGA_OK;
 }
 
+int jenga_requests_extend(jenga_pool* pool, int32_t kind, const int64_t* requests,
+                          const int64_t* new_lens, int32_t n) {
+  if (!kind_ok(pool, kind) || n < 0 || (n > 0 && (!requests || !new_lens))) return JENGA_ERR_INVALID;
+  for (int32_t i = 0; i < n; ++i) {
+    const int rc = jenga_request_extend(pool, requests[i], kind, new_lens[i]);
+    if (rc != JENGA_OK) return rc;
+  }
+  return JENGA_OK;
+}
+
+int jenga_block_table_fill(const jenga_pool* pool, int32_t kind, const int64_t* requests, int32_t n,
+                           int32_t* table, int32_t width) {
+  if (!kind_ok(pool, kind) || n < 0 || width < 0 || (n > 0 && (!requests || !table)))
+    return JENGA_ERR_INVALID;
+  for (int32_t i = 0; i < n; ++i) {
+    const int rc = jenga_request_block_table_row(pool, requests[i], kind, table + int64_t(i) * width, width);
+    if (rc != JENGA_OK) return rc;
+  }
+  return JENGA_OK;
+}
+
 const char* jenga_strerror(int status) {
   switch (status) {
     case JENGA_OK: return "ok";

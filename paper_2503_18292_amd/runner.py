@@ -38,7 +38,7 @@ class DecodeRunner:
 
     def __init__(self, cfg: ModelCfg, seed: int, device: str = "cuda:0",
                  ctx: Optional[np.ndarray] = None, pages_per_split: int = 0,
-                 script_seed: Optional[int] = None):
+                 script_seed: Optional[int] = None, step_budget: int = 0):
         if not torch.cuda.is_available():
             raise RuntimeError("DecodeRunner needs a GPU")
         self.cfg, self.seed, self.device = cfg, seed, torch.device(device)
@@ -58,6 +58,9 @@ class DecodeRunner:
         self.schedule = configs.layer_schedule(cfg)
         self.attn_kinds = sorted({k for k, _ in self.schedule})
         self._built = False
+        self.step_budget = step_budget           # further decode steps the tables must have room for
+        self._step_no = 0
+        self._pinned: Dict[int, list] = {}
         self.tables: Dict[int, torch.Tensor] = {}
         self.tables_host: Dict[int, torch.Tensor] = {}
         self.seq_lens: Dict[int, torch.Tensor] = {}
@@ -74,25 +77,55 @@ class DecodeRunner:
         self._built = True
 
     def host_step(self) -> None:
-        """Room for the new token, then block tables and lengths to the device."""
+        """Host side of one decode step: room for the new token of every request (one
+        allocator call per kind and request, new pages only when a page boundary is crossed;
+        window kinds drop pages that slid out), then block tables and lengths to the device."""
         assert self._built
-        scripts.run_script(scripts.step_script(self.cfg, self.ctx), self.pool)
+        B = self.cfg.batch
+        req_arr = np.asarray(self.requests, dtype=np.int64)
+        new_len = np.ascontiguousarray(self.ctx + 1, dtype=np.int64)
+        first = not self.tables
         for k in self.attn_kinds:
             kd = self.cfg.kinds[k]
             if kd.type == CROSS:
-                lens = np.full(self.cfg.batch, self.cfg.cross_len, dtype=np.int32)
+                if not first:
+                    continue                      # encoder K/V never changes after the first step
+                lens = np.full(B, self.cfg.cross_len, dtype=np.int32)
             else:
-                lens = (self.ctx + 1).astype(np.int32)
+                self.pool.requests_extend(k, req_arr, new_len)
+                lens = new_len.astype(np.int32)
             self.seq_lens_host[k] = lens
-            self.max_len[k] = int(lens.max())
-            width = -(-self.max_len[k] // kd.tokens_per_page)
-            tab = self.pool.block_table(self.requests, k, width)
+            if first:
+                cap = int(lens.max()) + (0 if kd.type == CROSS else self.step_budget)
+                self.max_len[k] = cap
+                width = -(-cap // kd.tokens_per_page)
+                self._pinned[k] = [(torch.empty(B, width, dtype=torch.int32).pin_memory(),
+                                    torch.empty(B, dtype=torch.int32).pin_memory(), None)
+                                   for _ in range(2)]
+                self.tables[k] = torch.empty(B, width, dtype=torch.int32, device=self.device)
+                self.seq_lens[k] = torch.empty(B, dtype=torch.int32, device=self.device)
+                ws = self.pool.decode_workspace_bytes(k, kd.n_q_heads, B, cap, kd.window,
+                                                      self.pages_per_split)
+                self.workspace[k] = torch.empty(ws // 4, dtype=torch.float32, device=self.device)
+            assert int(lens.max()) <= self.max_len[k], "step budget exhausted"
+            slot = self._step_no % 2
+            tab, ln, ev = self._pinned[k][slot]
+            if ev is not None:
+                ev.synchronize()                  # the copy that last used this staging buffer is done
+            self.pool.block_table_fill(k, req_arr, tab)
+            ln.copy_(torch.from_numpy(lens))
+            self.tables[k].copy_(tab, non_blocking=True)
+            self.seq_lens[k].copy_(ln, non_blocking=True)
+            ev = torch.cuda.Event()
+            ev.record()
+            self._pinned[k][slot] = (tab, ln, ev)
             self.tables_host[k] = tab
-            self.tables[k] = tab.to(self.device)
-            self.seq_lens[k] = torch.from_numpy(lens).to(self.device)
-            ws = self.pool.decode_workspace_bytes(k, kd.n_q_heads, self.cfg.batch, self.max_len[k],
-                                                  kd.window, self.pages_per_split)
-            self.workspace[k] = torch.empty(ws // 4, dtype=torch.float32, device=self.device)
+        self._step_no += 1
+
+    def advance(self) -> None:
+        """The next decode step: every request is one token longer."""
+        self.ctx = self.ctx + 1
+        self.host_step()
 
     # ---- data -------------------------------------------------------------------
     def fill_pool_random(self) -> None:
