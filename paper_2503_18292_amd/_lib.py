@@ -8,7 +8,8 @@ import ctypes as C
 import os
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "libjenga.so")
+# JENGA_LIB lets a developer point the binding at another build of the same library
+LIB_PATH = os.environ.get("JENGA_LIB") or os.path.join(HERE, "libjenga.so")
 
 c_i32, c_i64, c_f32, c_vp = C.c_int32, C.c_int64, C.c_float, C.c_void_p
 p_i32, p_i64 = C.POINTER(C.c_int32), C.POINTER(C.c_int64)

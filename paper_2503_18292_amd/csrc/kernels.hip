@@ -40,6 +40,7 @@ struct DecodeParams {
   const int32_t* block_table;
   int32_t bt_stride;
   const int32_t* seq_lens;
+  int32_t batch;
   int32_t max_seq_len;
   int32_t window;
   float scale_log2;           // softmax scale * log2(e): scores live in the base-2 domain
@@ -56,6 +57,61 @@ __device__ __forceinline__ void visible_pages(int L, int window, int t_log2, int
   *lo_tok = lo;
   *p_lo = lo >> t_log2;
   *p_hi = (L + (1 << t_log2) - 1) >> t_log2;
+}
+
+
+// Number of live split-K partitions of a request of length L.
+__device__ __forceinline__ int live_splits(int L, int window, int t_log2, int pages_per_split) {
+  if (L <= 0) return 0;
+  int lo_tok, p_lo, p_hi;
+  visible_pages(L, window, t_log2, &lo_tok, &p_lo, &p_hi);
+  return (p_hi - p_lo + pages_per_split - 1) / pages_per_split;
+}
+
+// Dense, XCD-aware task numbering.  The hardware deals consecutive blocks of the 1-D grid
+// round-robin to the 8 XCDs (each with its own L2 and address-translation cache).  Live
+// (request, partition) pairs are numbered densely as groups g = 0, 1, ...; group g runs on
+// XCD g % 8 with all its KV heads, so
+//   * the XCDs carry equal work whatever the mix of sequence lengths (a 3-D grid over
+//     (partition, head, request) sends all blocks of one partition index to one XCD whenever
+//     the partition count is a multiple of 8, and short requests leave the high partition
+//     indices empty: the XCDs then finish up to 20 % apart);
+//   * the KV heads of a page, which lie next to each other in the page's layer slice, are
+//     read through one XCD, so every page translation is needed on one XCD only.
+// Every block recomputes the prefix sum of live partitions from seq_lens, 64 requests per
+// pass: one coalesced load, the same latency as reading its own length.
+// Returns false for blocks past the last live group.
+__device__ __forceinline__ bool locate_task(const DecodeParams& p, int lane, int* b_out, int* split_out,
+                                            int* kvh_out, int* len_out) {
+  // hardware block t -> (group g of one (request, partition), KV head): blocks t, t+8, t+16, ...
+  // of a run of 8 * n_kv_heads blocks share g, so all KV heads of a page group run on one XCD
+  const int run = 8 * p.n_kv_heads;
+  const int r = blockIdx.x % run;
+  const int g = (blockIdx.x / run) * 8 + (r & 7);
+  *kvh_out = r >> 3;
+  int base = 0;
+  for (int c0 = 0; c0 < p.batch; c0 += kWave) {
+    const int i = c0 + lane;
+    const int Li = i < p.batch ? min(p.seq_lens[i], p.max_seq_len) : 0;
+    const int n = live_splits(Li, p.window, p.t_log2, p.pages_per_split);
+    int incl = n;
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+      const int up = __shfl_up(incl, off);
+      if (lane >= off) incl += up;
+    }
+    const int total = __builtin_amdgcn_readlane(incl, kWave - 1);
+    if (g < base + total) {
+      const unsigned long long hit = __ballot(base + incl > g);
+      const int who = __builtin_ctzll(hit);
+      *b_out = c0 + who;
+      *len_out = __builtin_amdgcn_readlane(Li, who);
+      *split_out = g - (base + __builtin_amdgcn_readlane(incl, who) - __builtin_amdgcn_readlane(n, who));
+      return true;
+    }
+    base += total;
+  }
+  return false;
 }
 
 // ---- cross-lane sums -------------------------------------------------------------
@@ -159,12 +215,8 @@ __global__ __launch_bounds__(kWave) void decode_partial_kernel(const DecodeParam
   constexpr int ROW = D * E::kBytes;       // bytes per token row
 
   const int lane = threadIdx.x;
-  const int split = blockIdx.x;
-  const int kvh = blockIdx.y;
-  const int b = blockIdx.z;
-
-  const int L = min(p.seq_lens[b], p.max_seq_len);
-  if (L <= 0) return;
+  int b, split, kvh, L;
+  if (!locate_task(p, lane, &b, &split, &kvh, &L)) return;
   int lo_tok, p_lo, p_hi;
   visible_pages(L, p.window, p.t_log2, &lo_tok, &p_lo, &p_hi);
   const int page0 = p_lo + split * p.pages_per_split;
@@ -322,6 +374,234 @@ __global__ __launch_bounds__(kWave) void decode_partial_kernel(const DecodeParam
   }
 }
 
+// ---- the decode kernel for 16-token pages ---------------------------------------------
+//
+// Same task decomposition and same results as the kernel above, with far fewer vector-ALU
+// instructions per byte.  The two operands are read in two different lane geometries:
+//
+//   K  lane l reads token l/4 of the page, the (l%4)-th 16 bytes of every 64-byte piece of
+//      that token's row (quads of lanes read 64 contiguous bytes).  A lane therefore sums
+//      a quarter of ONE token's dot product in its own registers and the only cross-lane
+//      work per score is a sum over 4 lanes.
+//   V  lane l reads 16 contiguous bytes at l*16 of every KiB of the page (as above), i.e.
+//      it owns EPL output elements and sees token (l / LPT) of each load.
+//
+// The softmax weights are produced in the K geometry (one token per quad of lanes) and
+// consumed in the V geometry, so they cross lanes through a small LDS array (broadcast
+// reads, no bank conflicts).  The running maximum is wave-uniform: it is reduced across the
+// wave once per tile and page, which also makes the final merge of the V lane groups a
+// plain sum.
+template <typename E, int D, int G>
+__global__ __launch_bounds__(kWave) void decode_partial_t16_kernel(const DecodeParams p) {
+  constexpr int T = 16;
+  constexpr int ROW = D * E::kBytes;            // bytes per token row
+  constexpr int EPL = 16 / E::kBytes;           // elements per 16 bytes
+  constexpr int KCH = ROW / 64;                 // 64-byte pieces per row == 1 KiB loads per page
+  constexpr int PPT = KCH >= 8 ? 1 : 8 / KCH;   // pages per tile
+  constexpr int NLD = PPT * KCH;                // loads per tile, K and V alike (8 or 16)
+  constexpr int LPT = ROW / 16;                 // V geometry: lanes per token row
+  constexpr int TPL = kWave / LPT;              // V geometry: tokens per load
+  constexpr int V_OFF = T * ROW;                // K rows come first in a (page, head) block
+
+  const int lane = threadIdx.x;
+  int b, split, kvh, L;
+  if (!locate_task(p, lane, &b, &split, &kvh, &L)) return;
+  int lo_tok, p_lo, p_hi;
+  visible_pages(L, p.window, 4, &lo_tok, &p_lo, &p_hi);
+  const int page0 = p_lo + split * p.pages_per_split;
+  if (page0 >= p_hi) return;
+  const int n_pages = min(p.pages_per_split, p_hi - page0);
+
+  __shared__ int32_t s_pages[kMaxPagesPerSplit];
+  __shared__ float s_prob[2][PPT * T][G];       // softmax weights of a tile, double buffered
+  for (int i = lane; i < n_pages; i += kWave)
+    s_pages[i] = p.block_table[int64_t(b) * p.bt_stride + page0 + i];
+  __syncthreads();
+
+  const int tok0 = page0 * T;
+  const int n_tiles = (n_pages + PPT - 1) / PPT;
+  const char* kv_base = p.layer_base + int64_t(kvh) * p.head_stride;   // wave-uniform
+  const unsigned k_voff = (lane >> 2) * ROW + (lane & 3) * 16;         // K geometry
+  const unsigned v_voff = V_OFF + lane * 16;                           // V geometry
+  const int k_tok = lane >> 2;                                         // token of the page this lane scores
+  const int v_grp = lane / LPT;
+
+  // query rows in the K geometry: for every 64-byte piece, this lane's 16 bytes
+  u32x4 qv[G][KCH];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    const char* qp = static_cast<const char*>(p.q) +
+                     (int64_t(b) * p.n_q_heads + kvh * G + g) * ROW + (lane & 3) * 16;
+#pragma unroll
+    for (int c = 0; c < KCH; ++c) qv[g][c] = *reinterpret_cast<const u32x4*>(qp + c * 64);
+  }
+
+  float m[G], l[G], acc[G][EPL];
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    m[g] = kNegBig;
+    l[g] = 0.f;
+#pragma unroll
+    for (int j = 0; j < EPL; ++j) acc[g][j] = 0.f;
+  }
+
+  // Page ids of the partition live in one register per stream, lane j holding page
+  // (chunk * 64 + j); v_readlane turns one into a scalar without an LDS round trip.
+  int pid_k = 0, pid_v = 0;
+  auto refill = [&](int page_rel, int& reg) {
+    if ((page_rel & 63) == 0) reg = (page_rel + lane < n_pages) ? s_pages[page_rel + lane] : 0;
+  };
+  auto page_ptr = [&](int page_rel, int reg) -> const char* {
+    const int sid = __builtin_amdgcn_readlane(reg, page_rel & 63);
+    return kv_base + int64_t(sid) * p.small_bytes;
+  };
+  auto load_k = [&](int tile, u32x4* buf) {
+    refill(tile * PPT, pid_k);
+#pragma unroll
+    for (int pp = 0; pp < PPT; ++pp) {
+      const int page_rel = tile * PPT + pp;
+      if (PPT == 1 || page_rel < n_pages) {
+        const char* pb = page_ptr(page_rel, pid_k);
+#pragma unroll
+        for (int c = 0; c < KCH; ++c)
+          buf[pp * KCH + c] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(pb + k_voff + c * 64));
+      } else {
+#pragma unroll
+        for (int c = 0; c < KCH; ++c) buf[pp * KCH + c] = u32x4{0, 0, 0, 0};
+      }
+    }
+  };
+  auto load_v = [&](int tile, u32x4* buf) {
+    refill(tile * PPT, pid_v);
+#pragma unroll
+    for (int pp = 0; pp < PPT; ++pp) {
+      const int page_rel = tile * PPT + pp;
+      if (PPT == 1 || page_rel < n_pages) {
+        const char* pb = page_ptr(page_rel, pid_v);
+#pragma unroll
+        for (int j = 0; j < KCH; ++j)
+          buf[pp * KCH + j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(pb + v_voff + j * 1024));
+      } else {
+#pragma unroll
+        for (int j = 0; j < KCH; ++j) buf[pp * KCH + j] = u32x4{0, 0, 0, 0};
+      }
+    }
+  };
+
+  u32x4 kbuf[NLD], vbuf[NLD];
+  load_k(0, kbuf);
+
+  for (int tile = 0; tile < n_tiles; ++tile) {
+    load_v(tile, vbuf);
+
+    // one score per (page of the tile, query head) and lane: token k_tok of that page
+    float s[PPT][G];
+#pragma unroll
+    for (int pp = 0; pp < PPT; ++pp)
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        float x = 0.f;
+#pragma unroll
+        for (int c = 0; c < KCH; ++c) x += dot16<E>(kbuf[pp * KCH + c], qv[g][c]);
+        x = dpp_add<0xB1>(x);      // lane ^ 1
+        x = dpp_add<0x4E>(x);      // lane ^ 2: all four lanes of the quad hold the token's score
+        s[pp][g] = x * p.scale_log2;
+      }
+
+    if (tile + 1 < n_tiles) load_k(tile + 1, kbuf);
+
+    const int tile_tok = tok0 + tile * PPT * T;           // first token of the tile
+    const bool clean = tile_tok >= lo_tok && tile_tok + PPT * T <= L;
+    if (!clean) {
+#pragma unroll
+      for (int pp = 0; pp < PPT; ++pp) {
+        const int t = tile_tok + pp * T + k_tok;
+        if (t < lo_tok || t >= L) {
+#pragma unroll
+          for (int g = 0; g < G; ++g) s[pp][g] = kNegBig;
+        }
+      }
+      // V rows outside the visible set may hold anything (even NaN): make them zero
+#pragma unroll
+      for (int i = 0; i < NLD; ++i) {
+        const int t = tile_tok + (i / KCH) * T + (i % KCH) * TPL + v_grp;
+        if (t < lo_tok || t >= L) vbuf[i] = u32x4{0, 0, 0, 0};
+      }
+    }
+
+    float (*prob)[G] = s_prob[tile & 1];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      float mx = s[0][g];
+#pragma unroll
+      for (int pp = 1; pp < PPT; ++pp) mx = fmaxf(mx, s[pp][g]);
+      // wave maximum: rows of 16 lanes first, then row -> next row broadcasts, lane 63 has it
+      mx = fmaxf(mx, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(mx), __float_as_int(mx), 0x124, 0xf, 0xf, false)));  // row_ror:4
+      mx = fmaxf(mx, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(mx), __float_as_int(mx), 0x128, 0xf, 0xf, false)));  // row_ror:8
+      mx = fmaxf(mx, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(mx), __float_as_int(mx), 0x142, 0xa, 0xf, false)));  // row_bcast:15
+      mx = fmaxf(mx, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(mx), __float_as_int(mx), 0x143, 0xc, 0xf, false)));  // row_bcast:31
+      const float tile_max = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(mx), 63));
+      const float m_new = fmaxf(m[g], tile_max);
+      const float alpha = __builtin_amdgcn_exp2f(m[g] - m_new);
+      float sum = 0.f;
+#pragma unroll
+      for (int pp = 0; pp < PPT; ++pp) {
+        float e = __builtin_amdgcn_exp2f(s[pp][g] - m_new);
+        if (!clean) e = (s[pp][g] == kNegBig) ? 0.f : e;
+        sum += e;
+        if ((lane & 3) == 0) prob[pp * T + k_tok][g] = e;
+      }
+      l[g] = fmaf(l[g], alpha, sum);
+      m[g] = m_new;
+#pragma unroll
+      for (int j = 0; j < EPL; ++j) acc[g][j] *= alpha;
+    }
+    __builtin_amdgcn_wave_barrier();
+
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+      const int t_in_tile = (i / KCH) * T + (i % KCH) * TPL + v_grp;
+      float w[G];
+#pragma unroll
+      for (int g = 0; g < G; ++g) w[g] = prob[t_in_tile][g];
+      float vf[EPL];
+      unpack16<E>(vbuf[i], vf);
+#pragma unroll
+      for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int j = 0; j < EPL; ++j) acc[g][j] = fmaf(w[g], vf[j], acc[g][j]);
+    }
+    __builtin_amdgcn_wave_barrier();
+  }
+
+  // every quad of lanes carried the same l; the V lane groups share m, so they just add up
+#pragma unroll
+  for (int g = 0; g < G; ++g) {
+    float lt = l[g];
+#pragma unroll
+    for (int off = 4; off < kWave; off <<= 1) lt += __shfl_xor(lt, off);
+    l[g] = lt;
+#pragma unroll
+    for (int off = LPT; off < kWave; off <<= 1)
+#pragma unroll
+      for (int j = 0; j < EPL; ++j) acc[g][j] += __shfl_xor(acc[g][j], off);
+  }
+
+  if (v_grp == 0) {
+    const int sub = lane % LPT;
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      const int64_t slot = (int64_t(b) * p.n_q_heads + kvh * G + g) * p.n_split + split;
+      float* dst = p.ws_acc + slot * D + sub * EPL;
+#pragma unroll
+      for (int j = 0; j < EPL; j += 4)
+        *reinterpret_cast<float4*>(dst + j) =
+            make_float4(acc[g][j], acc[g][j + 1], acc[g][j + 2], acc[g][j + 3]);
+      if (lane == 0) *reinterpret_cast<float2*>(p.ws_ml + slot * 2) = make_float2(m[g], l[g]);
+    }
+  }
+}
+
 // One block per (request, query head); thread i owns output elements [4i, 4i+4).
 template <int D>
 __global__ __launch_bounds__(D / 4) void splitk_reduce_kernel(
@@ -337,9 +617,7 @@ __global__ __launch_bounds__(D / 4) void splitk_reduce_kernel(
     *dst = make_float4(0.f, 0.f, 0.f, 0.f);
     return;
   }
-  int lo_tok, p_lo, p_hi;
-  visible_pages(L, window, t_log2, &lo_tok, &p_lo, &p_hi);
-  const int n_live = (p_hi - p_lo + pages_per_split - 1) / pages_per_split;
+  const int n_live = live_splits(L, window, t_log2, pages_per_split);
   const int64_t slot0 = (int64_t(b) * n_q_heads + hq) * n_split;
   float m_star = kNegBig;
   for (int s = 0; s < n_live; ++s) m_star = fmaxf(m_star, ws_ml[(slot0 + s) * 2]);
@@ -450,7 +728,7 @@ int split_geometry(const jenga::Kind& k, int batch, int max_seq_len, int window,
   if (pps > kMaxPagesPerSplit) return JENGA_ERR_INVALID;
   // keep the partition count within the grid limit
   int64_t n_split = (max_pages + pps - 1) / pps;
-  if (n_split > 65535) return JENGA_ERR_UNSUPPORTED;
+  if (n_split > (1 << 20)) return JENGA_ERR_UNSUPPORTED;
   out->pages_per_split = pps;
   out->n_split = int(n_split);
   return JENGA_OK;
@@ -474,7 +752,6 @@ int check_decode(const jenga_pool* pool, int32_t kind, int32_t n_q_heads, int32_
   if (!attention_kind(k)) return JENGA_ERR_INVALID;
   if (batch < 0 || batch > 65535 || max_seq_len < 0 || window < 0 || n_q_heads < 1)
     return JENGA_ERR_INVALID;
-  if (k.desc.n_kv_heads > 65535) return JENGA_ERR_UNSUPPORTED;
   if (n_q_heads % k.desc.n_kv_heads != 0) return JENGA_ERR_INVALID;
   const int G = n_q_heads / k.desc.n_kv_heads;
   if (G != 1 && G != 2 && G != 4 && G != 8) return JENGA_ERR_UNSUPPORTED;
@@ -487,6 +764,14 @@ int check_decode(const jenga_pool* pool, int32_t kind, int32_t n_q_heads, int32_
 
 template <typename E, int D>
 void launch_partial_g(int G, dim3 grid, hipStream_t st, const DecodeParams& p) {
+  if (p.t_log2 == 4 && G <= 4) {     // 16-token pages: the lane-per-token kernel
+    switch (G) {
+      case 1: hipLaunchKernelGGL((decode_partial_t16_kernel<E, D, 1>), grid, dim3(kWave), 0, st, p); break;
+      case 2: hipLaunchKernelGGL((decode_partial_t16_kernel<E, D, 2>), grid, dim3(kWave), 0, st, p); break;
+      default: hipLaunchKernelGGL((decode_partial_t16_kernel<E, D, 4>), grid, dim3(kWave), 0, st, p); break;
+    }
+    return;
+  }
   switch (G) {
     case 1: hipLaunchKernelGGL((decode_partial_kernel<E, D, 1>), grid, dim3(kWave), 0, st, p); break;
     case 2: hipLaunchKernelGGL((decode_partial_kernel<E, D, 2>), grid, dim3(kWave), 0, st, p); break;
@@ -597,6 +882,7 @@ int jenga_paged_decode_partial(const jenga_pool* pool, int32_t kind, int32_t lay
   p.block_table = block_table;
   p.bt_stride = bt_stride;
   p.seq_lens = seq_lens;
+  p.batch = batch;
   p.max_seq_len = max_seq_len;
   p.window = window;
   p.scale_log2 = scale * 1.4426950408889634f;
@@ -604,8 +890,11 @@ int jenga_paged_decode_partial(const jenga_pool* pool, int32_t kind, int32_t lay
   p.n_split = c.geom.n_split;
   p.ws_acc = acc;
   p.ws_ml = ml;
-  const dim3 grid(static_cast<unsigned>(c.geom.n_split), static_cast<unsigned>(k.desc.n_kv_heads),
-                  static_cast<unsigned>(batch));
+  // 1-D grid with room for every request at max_seq_len; blocks past the live tasks exit
+  const int64_t n_groups = (int64_t(c.geom.n_split) * batch + 7) / 8 * 8;    // whole runs of 8 groups
+  const int64_t n_blocks = n_groups * k.desc.n_kv_heads;
+  if (n_blocks > 0x7fffffff) return JENGA_ERR_UNSUPPORTED;
+  const dim3 grid(static_cast<unsigned>(n_blocks));
   hipStream_t st = static_cast<hipStream_t>(stream);
   if (k.desc.dtype == JENGA_F32)
     launch_partial_d<F32>(k.desc.head_dim, c.G, grid, st, p);

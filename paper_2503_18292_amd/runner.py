@@ -38,7 +38,8 @@ class DecodeRunner:
 
     def __init__(self, cfg: ModelCfg, seed: int, device: str = "cuda:0",
                  ctx: Optional[np.ndarray] = None, pages_per_split: int = 0,
-                 script_seed: Optional[int] = None, step_budget: int = 0):
+                 script_seed: Optional[int] = None, step_budget: int = 0,
+                 pool_u8: Optional[torch.Tensor] = None):
         if not torch.cuda.is_available():
             raise RuntimeError("DecodeRunner needs a GPU")
         self.cfg, self.seed, self.device = cfg, seed, torch.device(device)
@@ -51,7 +52,10 @@ class DecodeRunner:
         if n_large is None:
             n_large = scripts.pool_large_pages_needed(cfg, self.ctx, self.large_bytes)
         self.n_large = n_large
-        self.pool_u8 = torch.empty(n_large * self.large_bytes, dtype=torch.uint8, device=self.device)
+        if pool_u8 is None:
+            pool_u8 = torch.empty(n_large * self.large_bytes, dtype=torch.uint8, device=self.device)
+        assert pool_u8.numel() >= n_large * self.large_bytes      # device memory may be handed in
+        self.pool_u8 = pool_u8
         assert self.pool_u8.data_ptr() % 256 == 0
         self.pool = Pool(self.pool_u8.data_ptr(), self.pool_u8.numel(), self.descs)
         self.requests = [scripts.request_id(b) for b in range(cfg.batch)]
