@@ -186,15 +186,18 @@ int jenga_kv_append(const jenga_pool* pool, int32_t kind, int32_t layer,
                     const int32_t* block_table, int32_t bt_stride,
                     const int32_t* seq_lens, int32_t batch, jenga_stream stream);
 
-/* Number of split-K partitions per (request, KV head) the decode kernels will use for these
- * arguments, and the tokens per partition actually chosen.  pages_per_split = 0 lets the
- * library choose from batch, heads and max_seq_len.  Returns the split count (>= 1) or a
- * negative status. */
-int jenga_decode_num_splits(const jenga_pool* pool, int32_t kind, int32_t batch,
-                            int32_t max_seq_len, int32_t window, int32_t pages_per_split,
-                            int32_t* out_pages_per_split);
+/* Upper bound of the number of work partitions (wavefront tasks) the decode kernels use for
+ * these arguments.  The visible K/V of all (request, KV head) pairs, cut into tiles and laid
+ * end to end, is divided into equal partitions; pages_per_split = 0 lets the library take one
+ * partition per wavefront the device can hold at once (every wavefront then streams the same
+ * number of bytes whatever the mix of lengths), pages_per_split > 0 fixes the partition size.
+ * Returns the bound (>= 1) or a negative status. */
+int jenga_decode_num_partitions(const jenga_pool* pool, int32_t kind, int32_t n_q_heads,
+                                int32_t batch, int32_t max_seq_len, int32_t window,
+                                int32_t pages_per_split);
 /* Bytes of split-K workspace jenga_paged_decode needs for these arguments (> 0), or a
- * negative status. */
+ * negative status: one (max, sum, accumulator) record per query head for each of
+ * (partitions + batch * n_kv_heads) slots. */
 int64_t jenga_decode_workspace_bytes(const jenga_pool* pool, int32_t kind, int32_t n_q_heads,
                                      int32_t batch, int32_t max_seq_len, int32_t window,
                                      int32_t pages_per_split);
@@ -212,11 +215,11 @@ int64_t jenga_decode_workspace_bytes(const jenga_pool* pool, int32_t kind, int32
  *   seq_lens     device int32 [batch], each <= max_seq_len (larger ones are clamped)
  *   max_seq_len  host upper bound of seq_lens; sizes the grid; bt_stride * T >= max_seq_len
  *   window       0: none.  Pass the kind's window for WINDOW kinds.
- *   pages_per_split  0: automatic; else pages of K/V per split-K partition
+ *   pages_per_split  0: automatic (balanced partitions); else pages of K/V per partition
  *   workspace    device, >= jenga_decode_workspace_bytes(...), 16-byte aligned, caller-owned;
  *                holds per-partition (max, sum, accumulator) between the two kernels
  * Runs the partial kernel and the split-K reduction on `stream`.
- * Errors: INVALID, ALIGN, WORKSPACE, UNSUPPORTED (G not in {1,2,4,8}, head_dim), HIP. */
+ * Errors: INVALID, ALIGN, WORKSPACE, UNSUPPORTED (G not in {1,2,4,8}, batch > 1024), HIP. */
 int jenga_paged_decode(const jenga_pool* pool, int32_t kind, int32_t layer,
                        const void* q, int32_t n_q_heads,
                        const int32_t* block_table, int32_t bt_stride,

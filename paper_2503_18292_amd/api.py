@@ -199,13 +199,11 @@ class Pool:
                                          _ptr(block_table), block_table.shape[1], _ptr(seq_lens),
                                          seq_lens.shape[0], _stream()), "jenga_kv_append")
 
-    def decode_num_splits(self, kind: int, batch: int, max_seq_len: int, window: int = 0,
-                          pages_per_split: int = 0):
-        pps = C.c_int32(0)
-        n = _check(self._lib.jenga_decode_num_splits(self._h, kind, batch, max_seq_len, window,
-                                                     pages_per_split, C.byref(pps)),
-                   "jenga_decode_num_splits")
-        return n, pps.value
+    def decode_num_partitions(self, kind: int, n_q_heads: int, batch: int, max_seq_len: int,
+                              window: int = 0, pages_per_split: int = 0) -> int:
+        return _check(self._lib.jenga_decode_num_partitions(self._h, kind, n_q_heads, batch, max_seq_len,
+                                                            window, pages_per_split),
+                      "jenga_decode_num_partitions")
 
     def decode_workspace_bytes(self, kind: int, n_q_heads: int, batch: int, max_seq_len: int,
                                window: int = 0, pages_per_split: int = 0) -> int:

@@ -1,32 +1,51 @@
 // Device half of the library, written for gfx950 (CDNA4, 64-wide wavefronts).
 //
 //   kv_append_kernel       stores the new token's K/V rows into their page
-//   decode_partial_kernel  one wavefront per (request, KV head, split-K partition):
-//                          streams K and V pages with 16-byte loads, fp32 online
-//                          softmax, the G query heads of the group share every load
-//   splitk_reduce_kernel   log-sum-exp merge of the partitions
+//   decode_partial_kernel  streams K and V pages through a layer type's block table with
+//                          16-byte non-temporal loads, fp32 online softmax, the G query heads
+//                          of a KV head share every load; one wavefront per work partition
+//   splitk_reduce_kernel   log-sum-exp merge of the partitions of each (request, query head)
 //
-// Decode attention is a bandwidth-bound matrix-vector product (G flop per byte of
-// bf16 K/V), so no matrix-core instructions are used; the design goal is to keep
-// many 1 KiB wave-wide loads in flight per wavefront and to spend few vector-ALU
-// instructions per byte.
+// Decode attention is a bandwidth-bound matrix-vector product (G flop per byte of bf16 K/V),
+// so no matrix-core instructions are used.  What decides the speed is (1) that every
+// wavefront always has KiB-sized loads in flight, (2) that no wavefront idles while others
+// still work (work is cut into equal pieces, not into per-request pieces), and (3) few
+// vector-ALU instructions per byte.
 //
-// The kernel view of the pool is the one of paper Sec. 4.2: a start pointer (pool
-// base + layer offset), a page stride (the kind's small-page size) and page ids
-// (the kind's block table).
+// The kernel view of the pool is the one of paper Sec. 4.2: a start pointer (pool base +
+// layer offset), a page stride (the kind's small-page size) and page ids (the kind's block
+// table).
+//
+// Work partitioning ("flat" split-K).  The visible K/V of request b is cut into tiles (a
+// fixed number of tokens, one or a few pages).  All tiles of all (request, KV head) pairs are
+// laid end to end, request-major then head then token order, W tiles in total, and cut into
+// equal chunks of C tiles; wavefront w owns tiles [w*C, (w+1)*C).  A chunk usually lies inside
+// one (request, head) segment and sometimes spans the end of one and the start of the next;
+// for every segment it touches, the wavefront writes one partial record (running max, running
+// sum, un-normalised accumulator) to slot  segment_index + w  of the workspace: both terms
+// are non-decreasing along the flat order and one of them increases from one record to the
+// next, so slots never collide, and the records of a segment are consecutive.  With the
+// automatic chunk size C = ceil(W / partitions) every wavefront streams the same number of
+// bytes whatever the mix of sequence lengths, the grid is one resident wave of blocks, and
+// consecutive blocks -- which the hardware deals round-robin to the 8 XCDs -- carry equal
+// work.  W and the per-request offsets are recomputed by every block from seq_lens (one
+// coalesced load and a wave scan per 64 requests), so the host needs no knowledge of the
+// lengths and never synchronises.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
 #include <cstdint>
+#include <mutex>
+#include <unordered_map>
 
 #include "pool_internal.hpp"
 
 namespace {
 
 constexpr int kWave = 64;
-constexpr int kLoadsPerTile = 8;     // 16-byte loads per lane per K (or V) tile: 8 KiB per wave
-constexpr int kMaxPagesPerSplit = 256;
-constexpr float kNegBig = -1.0e30f;  // finite stand-in for -inf: keeps exp2(m - m) well defined
+constexpr int kMaxBatch = 1024;         // per-request prefix sums are kept in LDS
+constexpr int kMaxPartitions = 8192;    // bound of the automatic grid (sizes the workspace)
+constexpr float kNegBig = -1.0e30f;     // finite stand-in for -inf: keeps exp2(m - m) well defined
 
 struct DecodeParams {
   const char* layer_base;     // pool base + layer * slice_bytes
@@ -44,10 +63,10 @@ struct DecodeParams {
   int32_t max_seq_len;
   int32_t window;
   float scale_log2;           // softmax scale * log2(e): scores live in the base-2 domain
-  int32_t pages_per_split;
-  int32_t n_split;
-  float* ws_acc;              // [batch][n_q_heads][n_split][D]
-  float* ws_ml;               // [batch][n_q_heads][n_split][2]  (running max, running sum)
+  int32_t chunk_tiles;        // > 0: tiles per partition; 0: ceil(W / gridDim.x)
+  int32_t min_chunk_tiles;    // lower bound of the automatic chunk
+  float* ws_acc;              // [slot][G][D]
+  float* ws_ml;               // [slot][G][2]  (running max, running sum)
 };
 
 // Visible pages [p_lo, p_hi) and first visible token of a request of length L.
@@ -59,66 +78,76 @@ __device__ __forceinline__ void visible_pages(int L, int window, int t_log2, int
   *p_hi = (L + (1 << t_log2) - 1) >> t_log2;
 }
 
-
-// Number of live split-K partitions of a request of length L.
-__device__ __forceinline__ int live_splits(int L, int window, int t_log2, int pages_per_split) {
+// Tiles (of 2^tile_log2 tokens, counted from the first visible page) of a request.
+__device__ __forceinline__ int tiles_of(int L, int window, int t_log2, int tile_log2) {
   if (L <= 0) return 0;
   int lo_tok, p_lo, p_hi;
   visible_pages(L, window, t_log2, &lo_tok, &p_lo, &p_hi);
-  return (p_hi - p_lo + pages_per_split - 1) / pages_per_split;
+  return (((p_hi - p_lo) << t_log2) + (1 << tile_log2) - 1) >> tile_log2;
 }
 
-// Dense, XCD-aware task numbering.  The hardware deals consecutive blocks of the 1-D grid
-// round-robin to the 8 XCDs (each with its own L2 and address-translation cache).  Live
-// (request, partition) pairs are numbered densely as groups g = 0, 1, ...; group g runs on
-// XCD g % 8 with all its KV heads, so
-//   * the XCDs carry equal work whatever the mix of sequence lengths (a 3-D grid over
-//     (partition, head, request) sends all blocks of one partition index to one XCD whenever
-//     the partition count is a multiple of 8, and short requests leave the high partition
-//     indices empty: the XCDs then finish up to 20 % apart);
-//   * the KV heads of a page, which lie next to each other in the page's layer slice, are
-//     read through one XCD, so every page translation is needed on one XCD only.
-// Every block recomputes the prefix sum of live partitions from seq_lens, 64 requests per
-// pass: one coalesced load, the same latency as reading its own length.
-// Returns false for blocks past the last live group.
-__device__ __forceinline__ bool locate_task(const DecodeParams& p, int lane, int* b_out, int* split_out,
-                                            int* kvh_out, int* len_out) {
-  // hardware block t -> (group g of one (request, partition), KV head): blocks t, t+8, t+16, ...
-  // of a run of 8 * n_kv_heads blocks share g, so all KV heads of a page group run on one XCD
-  const int run = 8 * p.n_kv_heads;
-  const int r = blockIdx.x % run;
-  const int g = (blockIdx.x / run) * 8 + (r & 7);
-  *kvh_out = r >> 3;
-  int base = 0;
-  for (int c0 = 0; c0 < p.batch; c0 += kWave) {
+// Inclusive prefix sums of tiles * n_kv_heads per request into LDS, lengths next to them.
+// Returns W.  All 64 lanes of the (single-wave) block take part.
+__device__ __forceinline__ int scan_requests(const int32_t* seq_lens, int batch, int max_seq_len,
+                                             int window, int t_log2, int tile_log2, int n_kv_heads,
+                                             int lane, int* s_incl, int* s_len) {
+  int run = 0;
+  for (int c0 = 0; c0 < batch; c0 += kWave) {
     const int i = c0 + lane;
-    const int Li = i < p.batch ? min(p.seq_lens[i], p.max_seq_len) : 0;
-    const int n = live_splits(Li, p.window, p.t_log2, p.pages_per_split);
-    int incl = n;
+    const int Li = i < batch ? min(seq_lens[i], max_seq_len) : 0;
+    int incl = tiles_of(Li, window, t_log2, tile_log2) * n_kv_heads;
 #pragma unroll
     for (int off = 1; off < kWave; off <<= 1) {
       const int up = __shfl_up(incl, off);
       if (lane >= off) incl += up;
     }
-    const int total = __builtin_amdgcn_readlane(incl, kWave - 1);
-    if (g < base + total) {
-      const unsigned long long hit = __ballot(base + incl > g);
-      const int who = __builtin_ctzll(hit);
-      *b_out = c0 + who;
-      *len_out = __builtin_amdgcn_readlane(Li, who);
-      *split_out = g - (base + __builtin_amdgcn_readlane(incl, who) - __builtin_amdgcn_readlane(n, who));
-      return true;
+    if (i < batch) {
+      s_incl[i] = run + incl;
+      s_len[i] = Li;
     }
-    base += total;
+    run += __builtin_amdgcn_readlane(incl, kWave - 1);
   }
-  return false;
+  __syncthreads();
+  return run;
 }
 
-// ---- cross-lane sums -------------------------------------------------------------
+__device__ __forceinline__ int chunk_of(int chunk_tiles, int min_chunk_tiles, int W, int n_part) {
+  return chunk_tiles > 0 ? chunk_tiles : max(min_chunk_tiles, (W + n_part - 1) / n_part);
+}
+
+// First request whose inclusive prefix exceeds flat position x (x < W).
+__device__ __forceinline__ int find_request(const int* s_incl, int batch, int x, int lane) {
+  for (int c0 = 0; c0 < batch; c0 += kWave) {
+    const int i = c0 + lane;
+    const bool past = i < batch && s_incl[i] > x;
+    const unsigned long long hit = __ballot(past);
+    if (hit) return c0 + __builtin_ctzll(hit);
+  }
+  return batch - 1;
+}
+
+// ---- cross-lane helpers ------------------------------------------------------------
 template <int CTRL>
 __device__ __forceinline__ float dpp_add(float x) {
   const int y = __builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true);
   return x + __int_as_float(y);
+}
+
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_max(float x) {
+  const int y = __builtin_amdgcn_update_dpp(__float_as_int(x), __float_as_int(x), CTRL, ROW_MASK, 0xf, false);
+  return fmaxf(x, __int_as_float(y));
+}
+
+// Maximum over the wave, in an SGPR-uniform value.
+__device__ __forceinline__ float wave_max(float x) {
+  x = dpp_max<0xB1, 0xf>(x);    // lane ^ 1
+  x = dpp_max<0x4E, 0xf>(x);    // lane ^ 2
+  x = dpp_max<0x124, 0xf>(x);   // row_ror:4
+  x = dpp_max<0x128, 0xf>(x);   // row_ror:8  -> every lane holds its row's maximum
+  x = dpp_max<0x142, 0xa>(x);   // row_bcast:15 into rows 1 and 3
+  x = dpp_max<0x143, 0xc>(x);   // row_bcast:31 into rows 2 and 3 -> lane 63 holds the maximum
+  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), kWave - 1));
 }
 
 // Sum over aligned groups of LANES lanes, result in every lane of the group.
@@ -146,16 +175,14 @@ __device__ __forceinline__ float group_sum(float x) {
 
 // ---- element types ---------------------------------------------------------------
 struct F32 {
-  using storage = float;
   static constexpr int kBytes = 4;
 };
 struct BF16 {
-  using storage = uint16_t;
   static constexpr int kBytes = 2;
 };
 
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-typedef unsigned u32x4 __attribute__((ext_vector_type(4)));   // 16 bytes, a native vector so it can be loaded non-temporally
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));   // 16 bytes; a native vector, so it can be loaded non-temporally
 
 // <k, q> over the 16 bytes a lane holds.
 template <typename E>
@@ -195,444 +222,495 @@ __device__ __forceinline__ void unpack16(const u32x4& v, float* f) {
   }
 }
 
-// ---- the decode kernel -------------------------------------------------------------
-//
-// Lane geometry.  A token's K (or V) row is D*e bytes = LPT lanes x 16 bytes, so one
-// wave-wide 16-byte load covers TPL = 64 / LPT consecutive tokens (1 KiB, contiguous in
-// the page).  Lane l holds elements [sub*EPL, sub*EPL + EPL) of token (l / LPT) of the
-// load, sub = l % LPT.  A tile is kLoadsPerTile such loads of K and as many of V.
-//
-// Each group of LPT lanes runs its own online softmax over the tokens it sees (token
-// index mod TPL == its group), so the only cross-lane traffic in the loop is the sum of
-// the partial dot products inside a group; the TPL groups are merged once at the end.
-template <typename E, int D, int G>
-__global__ __launch_bounds__(kWave) void decode_partial_kernel(const DecodeParams p) {
-  constexpr int EPL = 16 / E::kBytes;
-  constexpr int LPT = D / EPL;
-  constexpr int TPL = kWave / LPT;
-  constexpr int NL = kLoadsPerTile;
-  constexpr int TT = NL * TPL;             // tokens per tile
-  constexpr int ROW = D * E::kBytes;       // bytes per token row
+// Page ids of the pages a wavefront is about to read, 128 at a time in two registers: lane j
+// of register (c & 1) holds the id of page 64*c + j (relative to the first page).  A
+// v_readlane turns one into a scalar, which makes the page's base address scalar too.  The
+// K stream runs one tile ahead of the V stream, so when K enters chunk c the register of
+// chunk c+1 (== that of chunk c-1, which V has just left) is reloaded.
+struct PageIds {
+  const int32_t* row;   // block-table entry of relative page 0
+  int n_pages;
+  int lane;
+  int reg[2];
 
-  const int lane = threadIdx.x;
-  int b, split, kvh, L;
-  if (!locate_task(p, lane, &b, &split, &kvh, &L)) return;
-  int lo_tok, p_lo, p_hi;
-  visible_pages(L, p.window, p.t_log2, &lo_tok, &p_lo, &p_hi);
-  const int page0 = p_lo + split * p.pages_per_split;
-  if (page0 >= p_hi) return;
-  const int n_pages = min(p.pages_per_split, p_hi - page0);
-
-  // block-table slice of this partition, staged once in LDS
-  __shared__ int32_t s_pages[kMaxPagesPerSplit];
-  for (int i = lane; i < n_pages; i += kWave)
-    s_pages[i] = p.block_table[int64_t(b) * p.bt_stride + page0 + i];
-  __syncthreads();
-
-  const int sub = lane % LPT;
-  const int grp = lane / LPT;
-  const int t_mask = (1 << p.t_log2) - 1;
-  const int tok0 = page0 << p.t_log2;                  // absolute index of the partition's first token
-  const int n_tok = n_pages << p.t_log2;
-  const int n_tiles = (n_tok + TT - 1) / TT;
-  const char* head_base = p.layer_base + int64_t(kvh) * p.head_stride + lane * 16;
-
-  // the G query rows of this KV head, 16 bytes per lane each
-  u32x4 qv[G];
-#pragma unroll
-  for (int g = 0; g < G; ++g) {
-    const char* qp = static_cast<const char*>(p.q) +
-                     (int64_t(b) * p.n_q_heads + kvh * G + g) * ROW + sub * 16;
-    qv[g] = *reinterpret_cast<const u32x4*>(qp);
+  __device__ __forceinline__ int fetch(int first) const {
+    const int i = first + lane;
+    return i < n_pages ? row[i] : 0;
   }
-
-  float m[G], l[G], acc[G][EPL];
-#pragma unroll
-  for (int g = 0; g < G; ++g) {
-    m[g] = kNegBig;
-    l[g] = 0.f;
-#pragma unroll
-    for (int j = 0; j < EPL; ++j) acc[g][j] = 0.f;
+  __device__ __forceinline__ void init(const int32_t* r, int n, int l) {
+    row = r; n_pages = n; lane = l;
+    reg[0] = fetch(0);
+    reg[1] = fetch(kWave);
   }
-
-  // Issues the loads of one tile of K (v_off = 0) or V (v_off = p.v_offset).
-  auto load_tile = [&](int tile, int v_off, u32x4* buf) {
-#pragma unroll
-    for (int i = 0; i < NL; ++i) {
-      const int tok = tile * TT + i * TPL;               // first token of this load, wave-uniform
-      const int page_rel = tok >> p.t_log2;
-      if (page_rel < n_pages) {
-        const int sid = __builtin_amdgcn_readfirstlane(s_pages[page_rel]);
-        const char* src = head_base + int64_t(sid) * p.small_bytes + v_off + (tok & t_mask) * ROW;
-        buf[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src));
-      } else {
-        buf[i] = u32x4{0, 0, 0, 0};
-      }
+  __device__ __forceinline__ int get(int page_rel) const {
+    const int r = (page_rel & kWave) ? reg[1] : reg[0];
+    return __builtin_amdgcn_readlane(r, page_rel & (kWave - 1));
+  }
+  // Call after the K stream has issued the loads of a tile starting at page_rel.
+  __device__ __forceinline__ void k_stream_at(int page_rel) {
+    if ((page_rel & (kWave - 1)) == 0 && page_rel > 0) {
+      if (page_rel & kWave) reg[0] = fetch(page_rel + kWave);
+      else reg[1] = fetch(page_rel + kWave);
     }
-  };
+  }
+};
 
-  u32x4 kbuf[NL], vbuf[NL];
-  load_tile(0, 0, kbuf);
-
-  for (int tile = 0; tile < n_tiles; ++tile) {
-    load_tile(tile, p.v_offset, vbuf);
-
-    // scores of the tile's tokens against the G query heads (base-2 logits)
-    float s[NL][G];
-#pragma unroll
-    for (int i = 0; i < NL; ++i)
-#pragma unroll
-      for (int g = 0; g < G; ++g)
-        s[i][g] = group_sum<LPT>(dot16<E>(kbuf[i], qv[g])) * p.scale_log2;
-
-    if (tile + 1 < n_tiles) load_tile(tile + 1, 0, kbuf);
-
-    // tokens of this lane's group that are outside [lo_tok, L) or past the partition
-    const int t_abs0 = tok0 + tile * TT + grp;
-    const bool clean = (tok0 + tile * TT >= lo_tok) && (tok0 + (tile + 1) * TT <= L) &&
-                       ((tile + 1) * TT <= n_tok);
-    bool valid[NL];
-#pragma unroll
-    for (int i = 0; i < NL; ++i) valid[i] = true;
-    if (!clean) {
-#pragma unroll
-      for (int i = 0; i < NL; ++i) {
-        const int t = t_abs0 + i * TPL;
-        valid[i] = (t >= lo_tok) && (t < L);
-        if (!valid[i]) {
-          vbuf[i] = u32x4{0, 0, 0, 0};             // masked rows may hold anything, even NaN
-#pragma unroll
-          for (int g = 0; g < G; ++g) s[i][g] = kNegBig;
-        }
-      }
-    }
-
-    float pr[NL][G];
+// Writes one partial record.  acc lives in the V lane geometry: lanes [0, LPT) hold EPL
+// consecutive output elements each.
+template <int D, int G, int EPL>
+__device__ __forceinline__ void store_partial(const DecodeParams& p, int64_t slot, int lane, int lpt,
+                                              const float (&m)[G], const float (&l)[G],
+                                              const float (&acc)[G][EPL]) {
+  if (lane < lpt) {
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-      float mx = s[0][g];
-#pragma unroll
-      for (int i = 1; i < NL; ++i) mx = fmaxf(mx, s[i][g]);
-      const float m_new = fmaxf(m[g], mx);
-      const float alpha = __builtin_amdgcn_exp2f(m[g] - m_new);
-      float sum = 0.f;
-#pragma unroll
-      for (int i = 0; i < NL; ++i) {
-        float e = __builtin_amdgcn_exp2f(s[i][g] - m_new);
-        if (!clean) e = valid[i] ? e : 0.f;
-        pr[i][g] = e;
-        sum += e;
-      }
-      l[g] = fmaf(l[g], alpha, sum);
-      m[g] = m_new;
-#pragma unroll
-      for (int j = 0; j < EPL; ++j) acc[g][j] *= alpha;
-    }
-
-#pragma unroll
-    for (int i = 0; i < NL; ++i) {
-      float vf[EPL];
-      unpack16<E>(vbuf[i], vf);
-#pragma unroll
-      for (int g = 0; g < G; ++g)
-#pragma unroll
-        for (int j = 0; j < EPL; ++j) acc[g][j] = fmaf(pr[i][g], vf[j], acc[g][j]);
-    }
-  }
-
-  // merge the TPL token groups (lanes that hold the same elements of different tokens)
-#pragma unroll
-  for (int off = LPT; off < kWave; off <<= 1) {
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-      const float m_o = __shfl_xor(m[g], off);
-      const float l_o = __shfl_xor(l[g], off);
-      const float m_new = fmaxf(m[g], m_o);
-      const float a = __builtin_amdgcn_exp2f(m[g] - m_new);
-      const float c = __builtin_amdgcn_exp2f(m_o - m_new);
-      l[g] = l[g] * a + l_o * c;
-      m[g] = m_new;
-#pragma unroll
-      for (int j = 0; j < EPL; ++j) {
-        const float acc_o = __shfl_xor(acc[g][j], off);
-        acc[g][j] = acc[g][j] * a + acc_o * c;
-      }
-    }
-  }
-
-  if (grp == 0) {
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-      const int64_t slot = (int64_t(b) * p.n_q_heads + kvh * G + g) * p.n_split + split;
-      float* dst = p.ws_acc + slot * D + sub * EPL;
+      float* dst = p.ws_acc + (slot * G + g) * D + lane * EPL;
 #pragma unroll
       for (int j = 0; j < EPL; j += 4)
         *reinterpret_cast<float4*>(dst + j) =
             make_float4(acc[g][j], acc[g][j + 1], acc[g][j + 2], acc[g][j + 3]);
-      if (lane == 0) *reinterpret_cast<float2*>(p.ws_ml + slot * 2) = make_float2(m[g], l[g]);
+      if (lane == 0) *reinterpret_cast<float2*>(p.ws_ml + (slot * G + g) * 2) = make_float2(m[g], l[g]);
     }
   }
 }
 
-// ---- the decode kernel for 16-token pages ---------------------------------------------
+// ---- engine for 16-token pages: one token per quad of lanes -----------------------------
 //
-// Same task decomposition and same results as the kernel above, with far fewer vector-ALU
-// instructions per byte.  The two operands are read in two different lane geometries:
-//
-//   K  lane l reads token l/4 of the page, the (l%4)-th 16 bytes of every 64-byte piece of
-//      that token's row (quads of lanes read 64 contiguous bytes).  A lane therefore sums
+// The two operands are read in two different lane geometries:
+//   K  lane l reads token l/4 of the page: the (l%4)-th 16 bytes of every 64-byte piece of
+//      that token's row (a quad of lanes reads 64 contiguous bytes).  A lane therefore sums
 //      a quarter of ONE token's dot product in its own registers and the only cross-lane
 //      work per score is a sum over 4 lanes.
-//   V  lane l reads 16 contiguous bytes at l*16 of every KiB of the page (as above), i.e.
-//      it owns EPL output elements and sees token (l / LPT) of each load.
-//
-// The softmax weights are produced in the K geometry (one token per quad of lanes) and
-// consumed in the V geometry, so they cross lanes through a small LDS array (broadcast
-// reads, no bank conflicts).  The running maximum is wave-uniform: it is reduced across the
-// wave once per tile and page, which also makes the final merge of the V lane groups a
-// plain sum.
-template <typename E, int D, int G>
-__global__ __launch_bounds__(kWave) void decode_partial_t16_kernel(const DecodeParams p) {
-  constexpr int T = 16;
-  constexpr int ROW = D * E::kBytes;            // bytes per token row
-  constexpr int EPL = 16 / E::kBytes;           // elements per 16 bytes
-  constexpr int KCH = ROW / 64;                 // 64-byte pieces per row == 1 KiB loads per page
-  constexpr int PPT = KCH >= 8 ? 1 : 8 / KCH;   // pages per tile
-  constexpr int NLD = PPT * KCH;                // loads per tile, K and V alike (8 or 16)
-  constexpr int LPT = ROW / 16;                 // V geometry: lanes per token row
-  constexpr int TPL = kWave / LPT;              // V geometry: tokens per load
-  constexpr int V_OFF = T * ROW;                // K rows come first in a (page, head) block
+//   V  lane l reads the 16 bytes at l*16 of every KiB of the page, i.e. it owns EPL output
+//      elements and sees token (l / LPT) of each load.
+// The softmax weights are produced in the K geometry (one token per quad) and consumed in
+// the V geometry, so they cross lanes through a small LDS array (broadcast reads, no bank
+// conflicts).  The running maximum is wave-uniform, which makes the final merge of the V
+// lane groups a plain sum.
+template <typename E_, int D_, int G_>
+struct QuadEngine {
+  using E = E_;
+  static constexpr int D = D_, G = G_;
+  static constexpr int T = 16;
+  static constexpr int ROW = D * E::kBytes;            // bytes per token row (<= 512 here)
+  static constexpr int EPL = 16 / E::kBytes;           // elements per 16 bytes
+  static constexpr int KCH = ROW / 64;                 // 64-byte pieces per row == 1 KiB loads per page
+  static constexpr int PPT = 8 / KCH;                  // pages per tile (1, 2 or 4)
+  static constexpr int NLD = 8;                        // loads per tile, K and V alike
+  static constexpr int LPT = ROW / 16;                 // V geometry: lanes per token row
+  static constexpr int TPL = kWave / LPT;              // V geometry: tokens per load
+  static constexpr int V_OFF = T * ROW;                // K rows come first in a (page, head) block
+  static constexpr int kTileLog2 = PPT == 1 ? 4 : PPT == 2 ? 5 : 6;
+  static constexpr int kLdsFloats = 2 * PPT * T * G;   // softmax weights of a tile, double buffered
+  static_assert(KCH >= 2 && KCH <= 8, "row size");
 
-  const int lane = threadIdx.x;
-  int b, split, kvh, L;
-  if (!locate_task(p, lane, &b, &split, &kvh, &L)) return;
-  int lo_tok, p_lo, p_hi;
-  visible_pages(L, p.window, 4, &lo_tok, &p_lo, &p_hi);
-  const int page0 = p_lo + split * p.pages_per_split;
-  if (page0 >= p_hi) return;
-  const int n_pages = min(p.pages_per_split, p_hi - page0);
+  __device__ static void run(const DecodeParams& p, int lane, int b, int kvh, int L, int tile0,
+                             int n_tiles, int64_t slot, float* lds) {
+    int lo_tok, p_lo, p_hi;
+    visible_pages(L, p.window, 4, &lo_tok, &p_lo, &p_hi);
+    const int page0 = p_lo + tile0 * PPT;
+    const int n_pages = min(n_tiles * PPT, p_hi - page0);
+    const int tok0 = page0 * T;
+    float (*s_prob)[PPT * T][G] = reinterpret_cast<float (*)[PPT * T][G]>(lds);
 
-  __shared__ int32_t s_pages[kMaxPagesPerSplit];
-  __shared__ float s_prob[2][PPT * T][G];       // softmax weights of a tile, double buffered
-  for (int i = lane; i < n_pages; i += kWave)
-    s_pages[i] = p.block_table[int64_t(b) * p.bt_stride + page0 + i];
-  __syncthreads();
+    PageIds ids;
+    ids.init(p.block_table + int64_t(b) * p.bt_stride + page0, n_pages, lane);
 
-  const int tok0 = page0 * T;
-  const int n_tiles = (n_pages + PPT - 1) / PPT;
-  const char* kv_base = p.layer_base + int64_t(kvh) * p.head_stride;   // wave-uniform
-  const unsigned k_voff = (lane >> 2) * ROW + (lane & 3) * 16;         // K geometry
-  const unsigned v_voff = V_OFF + lane * 16;                           // V geometry
-  const int k_tok = lane >> 2;                                         // token of the page this lane scores
-  const int v_grp = lane / LPT;
+    const char* kv_base = p.layer_base + int64_t(kvh) * p.head_stride;   // wave-uniform
+    const unsigned k_voff = (lane >> 2) * ROW + (lane & 3) * 16;         // K geometry
+    const unsigned v_voff = V_OFF + lane * 16;                           // V geometry
+    const int k_tok = lane >> 2;
+    const int v_grp = lane / LPT;
 
-  // query rows in the K geometry: for every 64-byte piece, this lane's 16 bytes
-  u32x4 qv[G][KCH];
+    // query rows in the K geometry: for every 64-byte piece, this lane's 16 bytes
+    u32x4 qv[G][KCH];
 #pragma unroll
-  for (int g = 0; g < G; ++g) {
-    const char* qp = static_cast<const char*>(p.q) +
-                     (int64_t(b) * p.n_q_heads + kvh * G + g) * ROW + (lane & 3) * 16;
+    for (int g = 0; g < G; ++g) {
+      const char* qp = static_cast<const char*>(p.q) +
+                       (int64_t(b) * p.n_q_heads + kvh * G + g) * ROW + (lane & 3) * 16;
 #pragma unroll
-    for (int c = 0; c < KCH; ++c) qv[g][c] = *reinterpret_cast<const u32x4*>(qp + c * 64);
-  }
-
-  float m[G], l[G], acc[G][EPL];
-#pragma unroll
-  for (int g = 0; g < G; ++g) {
-    m[g] = kNegBig;
-    l[g] = 0.f;
-#pragma unroll
-    for (int j = 0; j < EPL; ++j) acc[g][j] = 0.f;
-  }
-
-  // Page ids of the partition live in one register per stream, lane j holding page
-  // (chunk * 64 + j); v_readlane turns one into a scalar without an LDS round trip.
-  int pid_k = 0, pid_v = 0;
-  auto refill = [&](int page_rel, int& reg) {
-    if ((page_rel & 63) == 0) reg = (page_rel + lane < n_pages) ? s_pages[page_rel + lane] : 0;
-  };
-  auto page_ptr = [&](int page_rel, int reg) -> const char* {
-    const int sid = __builtin_amdgcn_readlane(reg, page_rel & 63);
-    return kv_base + int64_t(sid) * p.small_bytes;
-  };
-  auto load_k = [&](int tile, u32x4* buf) {
-    refill(tile * PPT, pid_k);
-#pragma unroll
-    for (int pp = 0; pp < PPT; ++pp) {
-      const int page_rel = tile * PPT + pp;
-      if (PPT == 1 || page_rel < n_pages) {
-        const char* pb = page_ptr(page_rel, pid_k);
-#pragma unroll
-        for (int c = 0; c < KCH; ++c)
-          buf[pp * KCH + c] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(pb + k_voff + c * 64));
-      } else {
-#pragma unroll
-        for (int c = 0; c < KCH; ++c) buf[pp * KCH + c] = u32x4{0, 0, 0, 0};
-      }
+      for (int c = 0; c < KCH; ++c) qv[g][c] = *reinterpret_cast<const u32x4*>(qp + c * 64);
     }
-  };
-  auto load_v = [&](int tile, u32x4* buf) {
-    refill(tile * PPT, pid_v);
+
+    float m[G], l[G], acc[G][EPL];
 #pragma unroll
-    for (int pp = 0; pp < PPT; ++pp) {
-      const int page_rel = tile * PPT + pp;
-      if (PPT == 1 || page_rel < n_pages) {
-        const char* pb = page_ptr(page_rel, pid_v);
+    for (int g = 0; g < G; ++g) {
+      m[g] = kNegBig;
+      l[g] = 0.f;
 #pragma unroll
-        for (int j = 0; j < KCH; ++j)
-          buf[pp * KCH + j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(pb + v_voff + j * 1024));
-      } else {
-#pragma unroll
-        for (int j = 0; j < KCH; ++j) buf[pp * KCH + j] = u32x4{0, 0, 0, 0};
-      }
+      for (int j = 0; j < EPL; ++j) acc[g][j] = 0.f;
     }
-  };
 
-  u32x4 kbuf[NLD], vbuf[NLD];
-  load_k(0, kbuf);
-
-  for (int tile = 0; tile < n_tiles; ++tile) {
-    load_v(tile, vbuf);
-
-    // one score per (page of the tile, query head) and lane: token k_tok of that page
-    float s[PPT][G];
-#pragma unroll
-    for (int pp = 0; pp < PPT; ++pp)
-#pragma unroll
-      for (int g = 0; g < G; ++g) {
-        float x = 0.f;
-#pragma unroll
-        for (int c = 0; c < KCH; ++c) x += dot16<E>(kbuf[pp * KCH + c], qv[g][c]);
-        x = dpp_add<0xB1>(x);      // lane ^ 1
-        x = dpp_add<0x4E>(x);      // lane ^ 2: all four lanes of the quad hold the token's score
-        s[pp][g] = x * p.scale_log2;
-      }
-
-    if (tile + 1 < n_tiles) load_k(tile + 1, kbuf);
-
-    const int tile_tok = tok0 + tile * PPT * T;           // first token of the tile
-    const bool clean = tile_tok >= lo_tok && tile_tok + PPT * T <= L;
-    if (!clean) {
+    auto load_pages = [&](int tile, unsigned voff, int step, u32x4* buf) {
 #pragma unroll
       for (int pp = 0; pp < PPT; ++pp) {
-        const int t = tile_tok + pp * T + k_tok;
-        if (t < lo_tok || t >= L) {
+        const int page_rel = tile * PPT + pp;
+        if (PPT == 1 || page_rel < n_pages) {
+          const char* pb = kv_base + int64_t(ids.get(page_rel)) * p.small_bytes;
 #pragma unroll
-          for (int g = 0; g < G; ++g) s[pp][g] = kNegBig;
+          for (int c = 0; c < KCH; ++c)
+            buf[pp * KCH + c] =
+                __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(pb + voff + c * step));
+        } else {
+#pragma unroll
+          for (int c = 0; c < KCH; ++c) buf[pp * KCH + c] = u32x4{0, 0, 0, 0};
         }
       }
-      // V rows outside the visible set may hold anything (even NaN): make them zero
+    };
+
+    u32x4 kbuf[NLD], vbuf[NLD];
+    load_pages(0, k_voff, 64, kbuf);
+
+    for (int tile = 0; tile < n_tiles; ++tile) {
+      load_pages(tile, v_voff, 1024, vbuf);
+
+      // one score per (page of the tile, query head) and lane: token k_tok of that page
+      float s[PPT][G];
+#pragma unroll
+      for (int pp = 0; pp < PPT; ++pp)
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+          float x = 0.f;
+#pragma unroll
+          for (int c = 0; c < KCH; ++c) x += dot16<E>(kbuf[pp * KCH + c], qv[g][c]);
+          x = dpp_add<0xB1>(x);      // lane ^ 1
+          x = dpp_add<0x4E>(x);      // lane ^ 2: all four lanes of the quad hold the token's score
+          s[pp][g] = x * p.scale_log2;
+        }
+
+      if (tile + 1 < n_tiles) {
+        load_pages(tile + 1, k_voff, 64, kbuf);
+        ids.k_stream_at((tile + 1) * PPT);
+      }
+
+      const int tile_tok = tok0 + tile * PPT * T;           // first token of the tile
+      const bool clean = tile_tok >= lo_tok && tile_tok + PPT * T <= L;
+      if (!clean) {
+#pragma unroll
+        for (int pp = 0; pp < PPT; ++pp) {
+          const int t = tile_tok + pp * T + k_tok;
+          if (t < lo_tok || t >= L) {
+#pragma unroll
+            for (int g = 0; g < G; ++g) s[pp][g] = kNegBig;
+          }
+        }
+        // V rows outside the visible set may hold anything (even NaN): make them zero
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+          const int t = tile_tok + (i / KCH) * T + (i % KCH) * TPL + v_grp;
+          if (t < lo_tok || t >= L) vbuf[i] = u32x4{0, 0, 0, 0};
+        }
+      }
+
+      float (*prob)[G] = s_prob[tile & 1];
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        float mx = s[0][g];
+#pragma unroll
+        for (int pp = 1; pp < PPT; ++pp) mx = fmaxf(mx, s[pp][g]);
+        const float m_new = fmaxf(m[g], wave_max(mx));
+        const float alpha = __builtin_amdgcn_exp2f(m[g] - m_new);
+        float sum = 0.f;
+#pragma unroll
+        for (int pp = 0; pp < PPT; ++pp) {
+          float e = __builtin_amdgcn_exp2f(s[pp][g] - m_new);
+          if (!clean) e = (s[pp][g] == kNegBig) ? 0.f : e;
+          sum += e;
+          if ((lane & 3) == 0) prob[pp * T + k_tok][g] = e;
+        }
+        l[g] = fmaf(l[g], alpha, sum);
+        m[g] = m_new;
+#pragma unroll
+        for (int j = 0; j < EPL; ++j) acc[g][j] *= alpha;
+      }
+      __builtin_amdgcn_wave_barrier();
+
 #pragma unroll
       for (int i = 0; i < NLD; ++i) {
-        const int t = tile_tok + (i / KCH) * T + (i % KCH) * TPL + v_grp;
-        if (t < lo_tok || t >= L) vbuf[i] = u32x4{0, 0, 0, 0};
+        const int t_in_tile = (i / KCH) * T + (i % KCH) * TPL + v_grp;
+        float w[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) w[g] = prob[t_in_tile][g];
+        float vf[EPL];
+        unpack16<E>(vbuf[i], vf);
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+          for (int j = 0; j < EPL; ++j) acc[g][j] = fmaf(w[g], vf[j], acc[g][j]);
       }
+      __builtin_amdgcn_wave_barrier();
     }
 
-    float (*prob)[G] = s_prob[tile & 1];
+    // every quad of lanes carried the same l; the V lane groups share m, so they just add up
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-      float mx = s[0][g];
+      float lt = l[g];
 #pragma unroll
-      for (int pp = 1; pp < PPT; ++pp) mx = fmaxf(mx, s[pp][g]);
-      // wave maximum: rows of 16 lanes first, then row -> next row broadcasts, lane 63 has it
-      mx = fmaxf(mx, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(mx), __float_as_int(mx), 0x124, 0xf, 0xf, false)));  // row_ror:4
-      mx = fmaxf(mx, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(mx), __float_as_int(mx), 0x128, 0xf, 0xf, false)));  // row_ror:8
-      mx = fmaxf(mx, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(mx), __float_as_int(mx), 0x142, 0xa, 0xf, false)));  // row_bcast:15
-      mx = fmaxf(mx, __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(mx), __float_as_int(mx), 0x143, 0xc, 0xf, false)));  // row_bcast:31
-      const float tile_max = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(mx), 63));
-      const float m_new = fmaxf(m[g], tile_max);
-      const float alpha = __builtin_amdgcn_exp2f(m[g] - m_new);
-      float sum = 0.f;
+      for (int off = 4; off < kWave; off <<= 1) lt += __shfl_xor(lt, off);
+      l[g] = lt;
 #pragma unroll
-      for (int pp = 0; pp < PPT; ++pp) {
-        float e = __builtin_amdgcn_exp2f(s[pp][g] - m_new);
-        if (!clean) e = (s[pp][g] == kNegBig) ? 0.f : e;
-        sum += e;
-        if ((lane & 3) == 0) prob[pp * T + k_tok][g] = e;
-      }
-      l[g] = fmaf(l[g], alpha, sum);
-      m[g] = m_new;
+      for (int off = LPT; off < kWave; off <<= 1)
 #pragma unroll
-      for (int j = 0; j < EPL; ++j) acc[g][j] *= alpha;
+        for (int j = 0; j < EPL; ++j) acc[g][j] += __shfl_xor(acc[g][j], off);
     }
-    __builtin_amdgcn_wave_barrier();
-
-#pragma unroll
-    for (int i = 0; i < NLD; ++i) {
-      const int t_in_tile = (i / KCH) * T + (i % KCH) * TPL + v_grp;
-      float w[G];
-#pragma unroll
-      for (int g = 0; g < G; ++g) w[g] = prob[t_in_tile][g];
-      float vf[EPL];
-      unpack16<E>(vbuf[i], vf);
-#pragma unroll
-      for (int g = 0; g < G; ++g)
-#pragma unroll
-        for (int j = 0; j < EPL; ++j) acc[g][j] = fmaf(w[g], vf[j], acc[g][j]);
-    }
-    __builtin_amdgcn_wave_barrier();
+    store_partial<D, G, EPL>(p, slot, lane, LPT, m, l, acc);
   }
+};
 
-  // every quad of lanes carried the same l; the V lane groups share m, so they just add up
-#pragma unroll
-  for (int g = 0; g < G; ++g) {
-    float lt = l[g];
-#pragma unroll
-    for (int off = 4; off < kWave; off <<= 1) lt += __shfl_xor(lt, off);
-    l[g] = lt;
-#pragma unroll
-    for (int off = LPT; off < kWave; off <<= 1)
-#pragma unroll
-      for (int j = 0; j < EPL; ++j) acc[g][j] += __shfl_xor(acc[g][j], off);
-  }
+// ---- engine for any page size: rows spread over lanes -----------------------------------
+//
+// K and V are read alike: a token's row is LPT lanes x 16 bytes, one wave-wide load covers
+// TPL = 64 / LPT consecutive tokens (1 KiB, contiguous in the page).  Every partial dot
+// product is summed over LPT lanes, so this engine spends several times more vector-ALU
+// work per byte than the one above; it covers what that one is not built for (pages of 8,
+// 32, 64 or 128 tokens, 8 query heads per KV head, 1 KiB rows).  Each group of LPT lanes runs
+// its own online softmax over the tokens it sees; the groups are merged once at the end.
+template <typename E_, int D_, int G_>
+struct RowEngine {
+  using E = E_;
+  static constexpr int D = D_, G = G_;
+  static constexpr int ROW = D * E::kBytes;
+  static constexpr int EPL = 16 / E::kBytes;
+  static constexpr int LPT = ROW / 16;
+  static constexpr int TPL = kWave / LPT;
+  static constexpr int NL = 8;                 // loads per tile
+  static constexpr int TT = NL * TPL;          // tokens per tile: 8, 16, 32 or 64
+  static constexpr int kTileLog2 = TT == 8 ? 3 : TT == 16 ? 4 : TT == 32 ? 5 : 6;
+  static constexpr int kLdsFloats = 0;
 
-  if (v_grp == 0) {
+  __device__ static void run(const DecodeParams& p, int lane, int b, int kvh, int L, int tile0,
+                             int n_tiles, int64_t slot, float*) {
+    int lo_tok, p_lo, p_hi;
+    visible_pages(L, p.window, p.t_log2, &lo_tok, &p_lo, &p_hi);
+    const int t_mask = (1 << p.t_log2) - 1;
+    // tiles are counted from the first visible page; a tile may be a fraction of a page
+    const int first_tok = tile0 * TT;                       // relative to page p_lo
+    const int page0 = p_lo + (first_tok >> p.t_log2);
+    const int tok_off0 = first_tok & t_mask;                // offset of the chunk inside page0
+    const int n_pages = min((tok_off0 + n_tiles * TT + t_mask) >> p.t_log2, p_hi - page0);
+    const int abs0 = (page0 << p.t_log2) + tok_off0;        // absolute index of the chunk's first token
+
+    PageIds ids;
+    ids.init(p.block_table + int64_t(b) * p.bt_stride + page0, n_pages, lane);
+
     const int sub = lane % LPT;
+    const int grp = lane / LPT;
+    const char* head_base = p.layer_base + int64_t(kvh) * p.head_stride + lane * 16;
+
+    u32x4 qv[G];
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-      const int64_t slot = (int64_t(b) * p.n_q_heads + kvh * G + g) * p.n_split + split;
-      float* dst = p.ws_acc + slot * D + sub * EPL;
-#pragma unroll
-      for (int j = 0; j < EPL; j += 4)
-        *reinterpret_cast<float4*>(dst + j) =
-            make_float4(acc[g][j], acc[g][j + 1], acc[g][j + 2], acc[g][j + 3]);
-      if (lane == 0) *reinterpret_cast<float2*>(p.ws_ml + slot * 2) = make_float2(m[g], l[g]);
+      const char* qp = static_cast<const char*>(p.q) +
+                       (int64_t(b) * p.n_q_heads + kvh * G + g) * ROW + sub * 16;
+      qv[g] = *reinterpret_cast<const u32x4*>(qp);
     }
+
+    float m[G], l[G], acc[G][EPL];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+      m[g] = kNegBig;
+      l[g] = 0.f;
+#pragma unroll
+      for (int j = 0; j < EPL; ++j) acc[g][j] = 0.f;
+    }
+
+    auto load_tile = [&](int tile, int v_off, u32x4* buf) {
+#pragma unroll
+      for (int i = 0; i < NL; ++i) {
+        const int tokr = tok_off0 + tile * TT + i * TPL;     // relative to page0, wave-uniform
+        const int page_rel = tokr >> p.t_log2;
+        if (page_rel < n_pages) {
+          const char* src = head_base + int64_t(ids.get(page_rel)) * p.small_bytes + v_off +
+                            (tokr & t_mask) * ROW;
+          buf[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src));
+        } else {
+          buf[i] = u32x4{0, 0, 0, 0};
+        }
+      }
+    };
+
+    u32x4 kbuf[NL], vbuf[NL];
+    load_tile(0, 0, kbuf);
+
+    for (int tile = 0; tile < n_tiles; ++tile) {
+      load_tile(tile, p.v_offset, vbuf);
+
+      float s[NL][G];
+#pragma unroll
+      for (int i = 0; i < NL; ++i)
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+          s[i][g] = group_sum<LPT>(dot16<E>(kbuf[i], qv[g])) * p.scale_log2;
+
+      if (tile + 1 < n_tiles) {
+        load_tile(tile + 1, 0, kbuf);
+        const int tokr = tok_off0 + (tile + 1) * TT;
+        if ((tokr & t_mask) == 0) ids.k_stream_at(tokr >> p.t_log2);
+      }
+
+      const int t_abs0 = abs0 + tile * TT + grp;
+      const bool clean = (abs0 + tile * TT >= lo_tok) && (abs0 + (tile + 1) * TT <= L);
+      bool valid[NL];
+#pragma unroll
+      for (int i = 0; i < NL; ++i) valid[i] = true;
+      if (!clean) {
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+          const int t = t_abs0 + i * TPL;
+          valid[i] = (t >= lo_tok) && (t < L);
+          if (!valid[i]) {
+            vbuf[i] = u32x4{0, 0, 0, 0};             // masked rows may hold anything, even NaN
+#pragma unroll
+            for (int g = 0; g < G; ++g) s[i][g] = kNegBig;
+          }
+        }
+      }
+
+      float pr[NL][G];
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        float mx = s[0][g];
+#pragma unroll
+        for (int i = 1; i < NL; ++i) mx = fmaxf(mx, s[i][g]);
+        const float m_new = fmaxf(m[g], mx);
+        const float alpha = __builtin_amdgcn_exp2f(m[g] - m_new);
+        float sum = 0.f;
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+          float e = __builtin_amdgcn_exp2f(s[i][g] - m_new);
+          if (!clean) e = valid[i] ? e : 0.f;
+          pr[i][g] = e;
+          sum += e;
+        }
+        l[g] = fmaf(l[g], alpha, sum);
+        m[g] = m_new;
+#pragma unroll
+        for (int j = 0; j < EPL; ++j) acc[g][j] *= alpha;
+      }
+
+#pragma unroll
+      for (int i = 0; i < NL; ++i) {
+        float vf[EPL];
+        unpack16<E>(vbuf[i], vf);
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+          for (int j = 0; j < EPL; ++j) acc[g][j] = fmaf(pr[i][g], vf[j], acc[g][j]);
+      }
+    }
+
+    // merge the TPL token groups (lanes that hold the same elements of different tokens)
+#pragma unroll
+    for (int off = LPT; off < kWave; off <<= 1) {
+#pragma unroll
+      for (int g = 0; g < G; ++g) {
+        const float m_o = __shfl_xor(m[g], off);
+        const float l_o = __shfl_xor(l[g], off);
+        const float m_new = fmaxf(m[g], m_o);
+        const float a = __builtin_amdgcn_exp2f(m[g] - m_new);
+        const float c = __builtin_amdgcn_exp2f(m_o - m_new);
+        l[g] = l[g] * a + l_o * c;
+        m[g] = m_new;
+#pragma unroll
+        for (int j = 0; j < EPL; ++j) {
+          const float acc_o = __shfl_xor(acc[g][j], off);
+          acc[g][j] = acc[g][j] * a + acc_o * c;
+        }
+      }
+    }
+    store_partial<D, G, EPL>(p, slot, lane, LPT, m, l, acc);
+  }
+};
+
+// One wavefront per partition of the flat tile space (see the head of the file).
+template <class Eng>
+__global__ __launch_bounds__(kWave) void decode_partial_kernel(const DecodeParams p) {
+  __shared__ int s_incl[kMaxBatch];
+  __shared__ int s_len[kMaxBatch];
+  __shared__ float s_eng[Eng::kLdsFloats > 0 ? Eng::kLdsFloats : 1];
+  const int lane = threadIdx.x;
+  const int W = scan_requests(p.seq_lens, p.batch, p.max_seq_len, p.window, p.t_log2, Eng::kTileLog2,
+                              p.n_kv_heads, lane, s_incl, s_len);
+  const int C = chunk_of(p.chunk_tiles, p.min_chunk_tiles, W, gridDim.x);
+  const int64_t x0 = int64_t(blockIdx.x) * C;
+  if (x0 >= W) return;
+  int x = int(x0);
+  const int x1 = int(min<int64_t>(W, x0 + C));
+  while (x < x1) {
+    const int b = find_request(s_incl, p.batch, x, lane);
+    const int start_b = b > 0 ? s_incl[b - 1] : 0;
+    const int tiles_b = (s_incl[b] - start_b) / p.n_kv_heads;
+    const int rem = x - start_b;
+    const int kvh = rem / tiles_b;
+    const int tile0 = rem - kvh * tiles_b;
+    const int xe = min(x1, start_b + (kvh + 1) * tiles_b);
+    const int64_t slot = int64_t(b) * p.n_kv_heads + kvh + blockIdx.x;
+    Eng::run(p, lane, b, kvh, s_len[b], tile0, xe - x, slot, s_eng);
+    x = xe;
   }
 }
 
-// One block per (request, query head); thread i owns output elements [4i, 4i+4).
+// One block (one wavefront) per (request, query head): merges the records of its segment,
+//   m* = max m_i,  out = sum_i acc_i 2^(m_i - m*) / sum_i l_i 2^(m_i - m*).
+// Thread i < D/4 owns output elements [4i, 4i+4); all 64 lanes take part in the scan.
 template <int D>
-__global__ __launch_bounds__(D / 4) void splitk_reduce_kernel(
+__global__ __launch_bounds__(kWave) void splitk_reduce_kernel(
     const float* __restrict__ ws_acc, const float* __restrict__ ws_ml,
-    const int32_t* __restrict__ seq_lens, int32_t max_seq_len, int32_t window, int32_t t_log2,
-    int32_t pages_per_split, int32_t n_split, int32_t n_q_heads, float* __restrict__ out) {
+    const int32_t* __restrict__ seq_lens, int32_t batch, int32_t max_seq_len, int32_t window,
+    int32_t t_log2, int32_t tile_log2, int32_t chunk_tiles, int32_t min_chunk_tiles, int32_t n_part,
+    int32_t n_kv_heads, int32_t n_q_heads, float* __restrict__ out) {
   const int hq = blockIdx.x;
   const int b = blockIdx.y;
-  const int tid = threadIdx.x;
-  float4* dst = reinterpret_cast<float4*>(out + (int64_t(b) * n_q_heads + hq) * D) + tid;
-  const int L = min(seq_lens[b], max_seq_len);
-  if (L <= 0) {
-    *dst = make_float4(0.f, 0.f, 0.f, 0.f);
+  const int lane = threadIdx.x;
+  const int G = n_q_heads / n_kv_heads;
+  // prefix of tiles * heads up to request b, and W
+  int run = 0, start_b = 0, tiles_b = 0;
+  for (int c0 = 0; c0 < batch; c0 += kWave) {
+    const int i = c0 + lane;
+    const int Li = i < batch ? min(seq_lens[i], max_seq_len) : 0;
+    const int n = tiles_of(Li, window, t_log2, tile_log2);
+    int incl = n * n_kv_heads;
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+      const int up = __shfl_up(incl, off);
+      if (lane >= off) incl += up;
+    }
+    if (b >= c0 && b < c0 + kWave) {
+      tiles_b = __builtin_amdgcn_readlane(n, b - c0);
+      start_b = run + __builtin_amdgcn_readlane(incl, b - c0) - tiles_b * n_kv_heads;
+    }
+    run += __builtin_amdgcn_readlane(incl, kWave - 1);
+  }
+  const bool owner = lane < D / 4;
+  float4* dst = reinterpret_cast<float4*>(out + (int64_t(b) * n_q_heads + hq) * D) + lane;
+  if (tiles_b == 0) {
+    if (owner) *dst = make_float4(0.f, 0.f, 0.f, 0.f);
     return;
   }
-  const int n_live = live_splits(L, window, t_log2, pages_per_split);
-  const int64_t slot0 = (int64_t(b) * n_q_heads + hq) * n_split;
+  const int C = chunk_of(chunk_tiles, min_chunk_tiles, run, n_part);
+  const int kvh = hq / G;
+  const int g = hq - kvh * G;
+  const int S = start_b + kvh * tiles_b;
+  const int c_lo = S / C;
+  const int c_hi = (S + tiles_b - 1) / C;
+  const int64_t seg = int64_t(b) * n_kv_heads + kvh;
   float m_star = kNegBig;
-  for (int s = 0; s < n_live; ++s) m_star = fmaxf(m_star, ws_ml[(slot0 + s) * 2]);
+  for (int c = c_lo; c <= c_hi; ++c) m_star = fmaxf(m_star, ws_ml[((seg + c) * G + g) * 2]);
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   float l_star = 0.f;
-  for (int s = 0; s < n_live; ++s) {
-    const float2 ml = *reinterpret_cast<const float2*>(ws_ml + (slot0 + s) * 2);
+  for (int c = c_lo; c <= c_hi; ++c) {
+    const int64_t rec = (seg + c) * G + g;
+    const float2 ml = *reinterpret_cast<const float2*>(ws_ml + rec * 2);
     const float w = __builtin_amdgcn_exp2f(ml.x - m_star);
-    const float4 a = *(reinterpret_cast<const float4*>(ws_acc + (slot0 + s) * D) + tid);
-    acc.x = fmaf(a.x, w, acc.x); acc.y = fmaf(a.y, w, acc.y);
-    acc.z = fmaf(a.z, w, acc.z); acc.w = fmaf(a.w, w, acc.w);
     l_star = fmaf(ml.y, w, l_star);
+    if (owner) {
+      const float4 a = *(reinterpret_cast<const float4*>(ws_acc + rec * D) + lane);
+      acc.x = fmaf(a.x, w, acc.x); acc.y = fmaf(a.y, w, acc.y);
+      acc.z = fmaf(a.z, w, acc.z); acc.w = fmaf(a.w, w, acc.w);
+    }
   }
   const float inv = l_star > 0.f ? 1.0f / l_star : 0.f;
-  *dst = make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv);
+  if (owner) *dst = make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv);
 }
 
 // One thread per 16 bytes of the new K and V rows.
@@ -682,7 +760,9 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const u32x4* __restric
   if (x == 0x9e3779b9u) *sink = x;     // practically never taken; keeps the loads alive
 }
 
-// ---- host side: validation, split geometry, launch ---------------------------------
+// ---- host side: validation, partition geometry, launch --------------------------------
+
+using DecodeFn = void (*)(DecodeParams);
 
 bool attention_kind(const jenga::Kind& k) {
   return k.desc.type == JENGA_FULL || k.desc.type == JENGA_WINDOW || k.desc.type == JENGA_CROSS;
@@ -690,115 +770,127 @@ bool attention_kind(const jenga::Kind& k) {
 
 bool aligned16(const void* p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; }
 
-// Tokens per tile of the decode kernel for this kind (see the lane geometry above).
-int tile_tokens(const jenga::Kind& k) {
-  const int lanes_per_token = k.desc.head_dim * k.elem_bytes / 16;
-  return kLoadsPerTile * (kWave / lanes_per_token);
-}
-
-struct SplitGeom {
-  int pages_per_split;
-  int n_split;
-};
-
-// Split-K geometry.  A partition is a whole number of pages and of tiles.  Automatic
-// choice: enough partitions to keep every SIMD of the 256 compute units busy with
-// several wavefronts, without making partitions so small that the workspace traffic
-// (one (D+2)-float record per partition and query head) shows up next to the K/V bytes.
-int split_geometry(const jenga::Kind& k, int batch, int max_seq_len, int window, int pages_per_split,
-                   SplitGeom* out) {
-  const int T = k.desc.tokens_per_page;
-  const int align = std::max(1, tile_tokens(k) / T);        // pages per tile
-  int64_t max_pages = (int64_t(max_seq_len) + T - 1) / T;
-  if (window > 0) max_pages = std::min<int64_t>(max_pages, window / T + 2);
-  max_pages = std::max<int64_t>(max_pages, 1);
-  int pps = pages_per_split;
-  if (pps < 0) return JENGA_ERR_INVALID;
-  if (pps == 0) {
-    const int64_t units = int64_t(std::max(batch, 1)) * k.desc.n_kv_heads * max_pages;
-    const int64_t target_partitions = 16384;
-    const int64_t bytes_per_page_head = k.slice_bytes / k.desc.n_kv_heads;
-    const int64_t min_pages = std::max<int64_t>(1, (128 * 1024) / bytes_per_page_head);  // >= 128 KiB each
-    int64_t want = (units + target_partitions - 1) / target_partitions;
-    want = std::max(want, min_pages);
-    want = std::min<int64_t>(want, kMaxPagesPerSplit);
-    pps = int(want);
-  }
-  pps = ((pps + align - 1) / align) * align;
-  if (pps > kMaxPagesPerSplit) return JENGA_ERR_INVALID;
-  // keep the partition count within the grid limit
-  int64_t n_split = (max_pages + pps - 1) / pps;
-  if (n_split > (1 << 20)) return JENGA_ERR_UNSUPPORTED;
-  out->pages_per_split = pps;
-  out->n_split = int(n_split);
-  return JENGA_OK;
-}
-
-int64_t workspace_bytes_for(const jenga::Kind& k, int n_q_heads, int batch, int n_split) {
-  const int64_t slots = int64_t(batch) * n_q_heads * n_split;
-  return slots * k.desc.head_dim * 4 + slots * 2 * 4;
-}
-
-struct DecodeCheck {
-  const jenga::Kind* kind;
-  SplitGeom geom;
-  int G;
-};
-
-int check_decode(const jenga_pool* pool, int32_t kind, int32_t n_q_heads, int32_t batch,
-                 int32_t max_seq_len, int32_t window, int32_t pages_per_split, DecodeCheck* out) {
-  if (!pool || kind < 0 || kind >= int32_t(pool->kinds.size())) return JENGA_ERR_INVALID;
-  const jenga::Kind& k = pool->kinds[kind];
-  if (!attention_kind(k)) return JENGA_ERR_INVALID;
-  if (batch < 0 || batch > 65535 || max_seq_len < 0 || window < 0 || n_q_heads < 1)
-    return JENGA_ERR_INVALID;
-  if (n_q_heads % k.desc.n_kv_heads != 0) return JENGA_ERR_INVALID;
-  const int G = n_q_heads / k.desc.n_kv_heads;
-  if (G != 1 && G != 2 && G != 4 && G != 8) return JENGA_ERR_UNSUPPORTED;
-  const int rc = split_geometry(k, batch, max_seq_len, window, pages_per_split, &out->geom);
-  if (rc != JENGA_OK) return rc;
-  out->kind = &k;
-  out->G = G;
-  return JENGA_OK;
-}
-
 template <typename E, int D>
-void launch_partial_g(int G, dim3 grid, hipStream_t st, const DecodeParams& p) {
-  if (p.t_log2 == 4 && G <= 4) {     // 16-token pages: the lane-per-token kernel
-    switch (G) {
-      case 1: hipLaunchKernelGGL((decode_partial_t16_kernel<E, D, 1>), grid, dim3(kWave), 0, st, p); break;
-      case 2: hipLaunchKernelGGL((decode_partial_t16_kernel<E, D, 2>), grid, dim3(kWave), 0, st, p); break;
-      default: hipLaunchKernelGGL((decode_partial_t16_kernel<E, D, 4>), grid, dim3(kWave), 0, st, p); break;
+DecodeFn pick_g(bool quad, int G) {
+  if constexpr (D * E::kBytes <= 512) {
+    if (quad) {
+      switch (G) {
+        case 1: return decode_partial_kernel<QuadEngine<E, D, 1>>;
+        case 2: return decode_partial_kernel<QuadEngine<E, D, 2>>;
+        default: return decode_partial_kernel<QuadEngine<E, D, 4>>;
+      }
     }
-    return;
   }
   switch (G) {
-    case 1: hipLaunchKernelGGL((decode_partial_kernel<E, D, 1>), grid, dim3(kWave), 0, st, p); break;
-    case 2: hipLaunchKernelGGL((decode_partial_kernel<E, D, 2>), grid, dim3(kWave), 0, st, p); break;
-    case 4: hipLaunchKernelGGL((decode_partial_kernel<E, D, 4>), grid, dim3(kWave), 0, st, p); break;
-    default: hipLaunchKernelGGL((decode_partial_kernel<E, D, 8>), grid, dim3(kWave), 0, st, p); break;
+    case 1: return decode_partial_kernel<RowEngine<E, D, 1>>;
+    case 2: return decode_partial_kernel<RowEngine<E, D, 2>>;
+    case 4: return decode_partial_kernel<RowEngine<E, D, 4>>;
+    default: return decode_partial_kernel<RowEngine<E, D, 8>>;
   }
 }
 
 template <typename E>
-void launch_partial_d(int D, int G, dim3 grid, hipStream_t st, const DecodeParams& p) {
+DecodeFn pick_d(int D, bool quad, int G) {
   switch (D) {
-    case 64: launch_partial_g<E, 64>(G, grid, st, p); break;
-    case 128: launch_partial_g<E, 128>(G, grid, st, p); break;
-    default: launch_partial_g<E, 256>(G, grid, st, p); break;
+    case 64: return pick_g<E, 64>(quad, G);
+    case 128: return pick_g<E, 128>(quad, G);
+    default: return pick_g<E, 256>(quad, G);
   }
+}
+
+// Blocks of `fn` that can be resident on the device at once (a multiple of 8, one share per
+// XCD), capped at kMaxPartitions.  Cached per kernel; 2048 when no device can be asked.
+int resident_partitions(DecodeFn fn) {
+  static std::mutex mu;
+  static std::unordered_map<const void*, int> cache;
+  std::lock_guard<std::mutex> lock(mu);
+  auto it = cache.find(reinterpret_cast<const void*>(fn));
+  if (it != cache.end()) return it->second;
+  int n = 2048;
+  int dev = 0, cus = 0, per_cu = 0;
+  if (hipGetDevice(&dev) == hipSuccess &&
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess &&
+      hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kWave, 0) == hipSuccess &&
+      cus > 0 && per_cu > 0) {
+    n = std::min(kMaxPartitions, cus * per_cu) / 8 * 8;
+    n = std::max(n, 8);
+    cache.emplace(reinterpret_cast<const void*>(fn), n);
+  } else {
+    (void)hipGetLastError();      // no device: do not leave a sticky error, do not cache
+  }
+  return n;
+}
+
+struct Geometry {
+  const jenga::Kind* kind;
+  int G;
+  bool quad;
+  int tile_log2;
+  int chunk_tiles;       // 0: automatic
+  int min_chunk_tiles;
+  int n_part_bound;      // partitions the workspace must have room for
+  int64_t slots;
+  DecodeFn fn;
+};
+
+// Everything the partial kernel and the reduction must agree on.
+int decode_geometry(const jenga_pool* pool, int32_t kind, int32_t n_q_heads, int32_t batch,
+                    int32_t max_seq_len, int32_t window, int32_t pages_per_split, Geometry* out) {
+  if (!pool || kind < 0 || kind >= int32_t(pool->kinds.size())) return JENGA_ERR_INVALID;
+  const jenga::Kind& k = pool->kinds[kind];
+  if (!attention_kind(k)) return JENGA_ERR_INVALID;
+  if (batch < 0 || max_seq_len < 0 || window < 0 || n_q_heads < 1 || pages_per_split < 0)
+    return JENGA_ERR_INVALID;
+  if (batch > kMaxBatch) return JENGA_ERR_UNSUPPORTED;
+  if (n_q_heads % k.desc.n_kv_heads != 0) return JENGA_ERR_INVALID;
+  const int G = n_q_heads / k.desc.n_kv_heads;
+  if (G != 1 && G != 2 && G != 4 && G != 8) return JENGA_ERR_UNSUPPORTED;
+  const int row = k.desc.head_dim * k.elem_bytes;
+  const int T = k.desc.tokens_per_page;
+  out->kind = &k;
+  out->G = G;
+  out->quad = (k.t_log2 == 4 && G <= 4 && row <= 512);
+  const int tile_tokens = out->quad ? (8 / (row / 64)) * 16 : 8 * (kWave / (row / 16));
+  out->tile_log2 = 0;
+  while ((1 << out->tile_log2) < tile_tokens) ++out->tile_log2;
+  int64_t max_pages = (int64_t(max_seq_len) + T - 1) / T;
+  if (window > 0) max_pages = std::min<int64_t>(max_pages, window / T + 2);
+  const int64_t max_tiles = (max_pages * T + tile_tokens - 1) / tile_tokens;
+  const int64_t w_max = max_tiles * k.desc.n_kv_heads * std::max(batch, 1);
+  if (w_max > 0x3fffffff) return JENGA_ERR_UNSUPPORTED;
+  out->fn = k.desc.dtype == JENGA_F32 ? pick_d<F32>(k.desc.head_dim, out->quad, G)
+                                      : pick_d<BF16>(k.desc.head_dim, out->quad, G);
+  const int64_t tile_bytes = int64_t(tile_tokens) * row * 2;
+  out->min_chunk_tiles = int(std::max<int64_t>(1, (64 * 1024) / tile_bytes));
+  if (pages_per_split > 0) {
+    out->chunk_tiles = int(std::max<int64_t>(1, int64_t(pages_per_split) * T / tile_tokens));
+    const int64_t n = std::max<int64_t>(1, (w_max + out->chunk_tiles - 1) / out->chunk_tiles);
+    if (n > (1 << 22)) return JENGA_ERR_UNSUPPORTED;
+    out->n_part_bound = int(n);
+  } else {
+    out->chunk_tiles = 0;
+    out->n_part_bound = kMaxPartitions;
+  }
+  out->slots = int64_t(out->n_part_bound) + int64_t(std::max(batch, 1)) * k.desc.n_kv_heads;
+  return JENGA_OK;
+}
+
+int launch_partitions(const Geometry& g) {
+  return g.chunk_tiles > 0 ? g.n_part_bound : resident_partitions(g.fn);
+}
+
+int64_t workspace_bytes_for(const Geometry& g) {
+  return g.slots * g.G * (g.kind->desc.head_dim + 2) * 4;
 }
 
 int hip_status() { return hipGetLastError() == hipSuccess ? JENGA_OK : JENGA_ERR_HIP; }
 
-int split_ws(const jenga::Kind& k, int n_q_heads, int batch, int n_split, void* workspace,
-             int64_t workspace_bytes, float** acc, float** ml) {
+int split_ws(const Geometry& g, void* workspace, int64_t workspace_bytes, float** acc, float** ml) {
   if (!workspace) return JENGA_ERR_INVALID;
   if (!aligned16(workspace)) return JENGA_ERR_ALIGN;
-  if (workspace_bytes < workspace_bytes_for(k, n_q_heads, batch, n_split)) return JENGA_ERR_WORKSPACE;
-  const int64_t slots = int64_t(batch) * n_q_heads * n_split;
+  if (workspace_bytes < workspace_bytes_for(g)) return JENGA_ERR_WORKSPACE;
   *acc = static_cast<float*>(workspace);
-  *ml = *acc + slots * k.desc.head_dim;
+  *ml = *acc + g.slots * g.G * g.kind->desc.head_dim;
   return JENGA_OK;
 }
 
@@ -830,24 +922,21 @@ int jenga_kv_append(const jenga_pool* pool, int32_t kind, int32_t layer, const v
   return hip_status();
 }
 
-int jenga_decode_num_splits(const jenga_pool* pool, int32_t kind, int32_t batch, int32_t max_seq_len,
-                            int32_t window, int32_t pages_per_split, int32_t* out_pages_per_split) {
-  DecodeCheck c;
-  if (!pool || kind < 0 || kind >= int32_t(pool->kinds.size())) return JENGA_ERR_INVALID;
-  const int rc = check_decode(pool, kind, pool->kinds[kind].desc.n_kv_heads, batch, max_seq_len,
-                              window, pages_per_split, &c);
+int jenga_decode_num_partitions(const jenga_pool* pool, int32_t kind, int32_t n_q_heads, int32_t batch,
+                                int32_t max_seq_len, int32_t window, int32_t pages_per_split) {
+  Geometry g;
+  const int rc = decode_geometry(pool, kind, n_q_heads, batch, max_seq_len, window, pages_per_split, &g);
   if (rc != JENGA_OK) return rc;
-  if (out_pages_per_split) *out_pages_per_split = c.geom.pages_per_split;
-  return c.geom.n_split;
+  return g.n_part_bound;
 }
 
 int64_t jenga_decode_workspace_bytes(const jenga_pool* pool, int32_t kind, int32_t n_q_heads,
                                      int32_t batch, int32_t max_seq_len, int32_t window,
                                      int32_t pages_per_split) {
-  DecodeCheck c;
-  const int rc = check_decode(pool, kind, n_q_heads, batch, max_seq_len, window, pages_per_split, &c);
+  Geometry g;
+  const int rc = decode_geometry(pool, kind, n_q_heads, batch, max_seq_len, window, pages_per_split, &g);
   if (rc != JENGA_OK) return rc;
-  return std::max<int64_t>(16, workspace_bytes_for(*c.kind, n_q_heads, batch, c.geom.n_split));
+  return workspace_bytes_for(g);
 }
 
 int jenga_paged_decode_partial(const jenga_pool* pool, int32_t kind, int32_t layer, const void* q,
@@ -855,17 +944,17 @@ int jenga_paged_decode_partial(const jenga_pool* pool, int32_t kind, int32_t lay
                                const int32_t* seq_lens, int32_t batch, int32_t max_seq_len,
                                int32_t window, float scale, int32_t pages_per_split, void* workspace,
                                int64_t workspace_bytes, jenga_stream stream) {
-  DecodeCheck c;
-  int rc = check_decode(pool, kind, n_q_heads, batch, max_seq_len, window, pages_per_split, &c);
+  Geometry g;
+  int rc = decode_geometry(pool, kind, n_q_heads, batch, max_seq_len, window, pages_per_split, &g);
   if (rc != JENGA_OK) return rc;
-  const jenga::Kind& k = *c.kind;
+  const jenga::Kind& k = *g.kind;
   if (!pool->base || layer < 0 || layer >= k.desc.n_layers || !q || !block_table || !seq_lens ||
       bt_stride < 1)
     return JENGA_ERR_INVALID;
   if (int64_t(bt_stride) * k.desc.tokens_per_page < max_seq_len) return JENGA_ERR_INVALID;
   if (!aligned16(q)) return JENGA_ERR_ALIGN;
   float *acc = nullptr, *ml = nullptr;
-  rc = split_ws(k, n_q_heads, batch, c.geom.n_split, workspace, workspace_bytes, &acc, &ml);
+  rc = split_ws(g, workspace, workspace_bytes, &acc, &ml);
   if (rc != JENGA_OK) return rc;
   if (batch == 0) return JENGA_OK;
 
@@ -886,20 +975,12 @@ int jenga_paged_decode_partial(const jenga_pool* pool, int32_t kind, int32_t lay
   p.max_seq_len = max_seq_len;
   p.window = window;
   p.scale_log2 = scale * 1.4426950408889634f;
-  p.pages_per_split = c.geom.pages_per_split;
-  p.n_split = c.geom.n_split;
+  p.chunk_tiles = g.chunk_tiles;
+  p.min_chunk_tiles = g.min_chunk_tiles;
   p.ws_acc = acc;
   p.ws_ml = ml;
-  // 1-D grid with room for every request at max_seq_len; blocks past the live tasks exit
-  const int64_t n_groups = (int64_t(c.geom.n_split) * batch + 7) / 8 * 8;    // whole runs of 8 groups
-  const int64_t n_blocks = n_groups * k.desc.n_kv_heads;
-  if (n_blocks > 0x7fffffff) return JENGA_ERR_UNSUPPORTED;
-  const dim3 grid(static_cast<unsigned>(n_blocks));
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  if (k.desc.dtype == JENGA_F32)
-    launch_partial_d<F32>(k.desc.head_dim, c.G, grid, st, p);
-  else
-    launch_partial_d<BF16>(k.desc.head_dim, c.G, grid, st, p);
+  const int n_part = launch_partitions(g);
+  hipLaunchKernelGGL(g.fn, dim3(unsigned(n_part)), dim3(kWave), 0, static_cast<hipStream_t>(stream), p);
   return hip_status();
 }
 
@@ -907,36 +988,29 @@ int jenga_splitk_reduce(const jenga_pool* pool, int32_t kind, int32_t n_q_heads,
                         const int32_t* seq_lens, int32_t batch, int32_t max_seq_len, int32_t window,
                         int32_t pages_per_split, const void* workspace, int64_t workspace_bytes,
                         float* out, jenga_stream stream) {
-  DecodeCheck c;
-  int rc = check_decode(pool, kind, n_q_heads, batch, max_seq_len, window, pages_per_split, &c);
+  Geometry g;
+  int rc = decode_geometry(pool, kind, n_q_heads, batch, max_seq_len, window, pages_per_split, &g);
   if (rc != JENGA_OK) return rc;
-  const jenga::Kind& k = *c.kind;
+  const jenga::Kind& k = *g.kind;
   if (!seq_lens || !out) return JENGA_ERR_INVALID;
   if (!aligned16(out)) return JENGA_ERR_ALIGN;
   float *acc = nullptr, *ml = nullptr;
-  rc = split_ws(k, n_q_heads, batch, c.geom.n_split, const_cast<void*>(workspace), workspace_bytes,
-                &acc, &ml);
+  rc = split_ws(g, const_cast<void*>(workspace), workspace_bytes, &acc, &ml);
   if (rc != JENGA_OK) return rc;
   if (batch == 0) return JENGA_OK;
+  const int n_part = launch_partitions(g);
   const dim3 grid(static_cast<unsigned>(n_q_heads), static_cast<unsigned>(batch));
   hipStream_t st = static_cast<hipStream_t>(stream);
+#define JENGA_LAUNCH_REDUCE(DIM)                                                                   \
+  hipLaunchKernelGGL((splitk_reduce_kernel<DIM>), grid, dim3(kWave), 0, st, acc, ml, seq_lens,    \
+                     batch, max_seq_len, window, k.t_log2, g.tile_log2, g.chunk_tiles,             \
+                     g.min_chunk_tiles, n_part, k.desc.n_kv_heads, n_q_heads, out)
   switch (k.desc.head_dim) {
-    case 64:
-      hipLaunchKernelGGL((splitk_reduce_kernel<64>), grid, dim3(16), 0, st, acc, ml, seq_lens,
-                         max_seq_len, window, k.t_log2, c.geom.pages_per_split, c.geom.n_split,
-                         n_q_heads, out);
-      break;
-    case 128:
-      hipLaunchKernelGGL((splitk_reduce_kernel<128>), grid, dim3(32), 0, st, acc, ml, seq_lens,
-                         max_seq_len, window, k.t_log2, c.geom.pages_per_split, c.geom.n_split,
-                         n_q_heads, out);
-      break;
-    default:
-      hipLaunchKernelGGL((splitk_reduce_kernel<256>), grid, dim3(64), 0, st, acc, ml, seq_lens,
-                         max_seq_len, window, k.t_log2, c.geom.pages_per_split, c.geom.n_split,
-                         n_q_heads, out);
-      break;
+    case 64: JENGA_LAUNCH_REDUCE(64); break;
+    case 128: JENGA_LAUNCH_REDUCE(128); break;
+    default: JENGA_LAUNCH_REDUCE(256); break;
   }
+#undef JENGA_LAUNCH_REDUCE
   return hip_status();
 }
 

@@ -206,19 +206,25 @@ def test_error_paths():
     assert pool._lib.jenga_decode_workspace_bytes(pool._h, 0, 4, 1, 16, 0, 0) == -1
 
 
-def test_split_geometry_and_workspace_queries():
+def test_partition_geometry_and_workspace_queries():
     cfg = configs.gemma2_9b()
     lib = make_library(cfg, 4)
-    n, pps = lib.decode_num_splits(0, 64, 8193)
-    assert n == -(-513 // pps) and pps >= 1
-    ws = lib.decode_workspace_bytes(0, 16, 64, 8193)
-    assert ws == 64 * 16 * n * (256 + 2) * 4
-    nw, ppsw = lib.decode_num_splits(1, 64, 8193, window=4096)
-    assert nw * ppsw >= 4096 // 16 + 1 and nw < n
-    n1, pps1 = lib.decode_num_splits(0, 64, 8193, pages_per_split=32)
-    assert pps1 == 32 and n1 == -(-513 // 32)
-    with pytest.raises(J.JengaError):
-        lib.decode_num_splits(0, 64, 8193, pages_per_split=100000)
+    # automatic: a fixed bound, independent of the lengths
+    n = lib.decode_num_partitions(0, 16, 64, 8193)
+    assert n == 8192
+    assert lib.decode_workspace_bytes(0, 16, 64, 8193) == (n + 64 * 8) * 2 * (256 + 2) * 4
+    # explicit partition size: 513 pages of 16 tokens, one page per tile, 32 pages per partition
+    n32 = lib.decode_num_partitions(0, 16, 64, 8193, pages_per_split=32)
+    assert n32 == -(-(513 * 8 * 64) // 32)
+    assert lib.decode_workspace_bytes(0, 16, 64, 8193, pages_per_split=32) == (n32 + 512) * 2 * 258 * 4
+    # a window bounds the visible pages
+    nw = lib.decode_num_partitions(1, 16, 64, 8193, window=4096, pages_per_split=32)
+    assert nw == -(-((4096 // 16 + 2) * 8 * 64) // 32)
     with pytest.raises(J.JengaError) as e:
         lib.decode_workspace_bytes(0, 24, 64, 8193)      # 24 query heads over 8 KV heads: G = 3
     assert e.value.status == -6
+    with pytest.raises(J.JengaError) as e:
+        lib.decode_workspace_bytes(0, 16, 5000, 8193)    # batch beyond the kernels' limit
+    assert e.value.status == -6
+    with pytest.raises(J.JengaError):
+        lib.decode_workspace_bytes(0, 16, 64, 8193, pages_per_split=-1)
