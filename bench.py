@@ -55,26 +55,29 @@ def cpu_baseline(runner, budget_s: float):
     torch.cuda.synchronize()
     t_used, nbytes, n_units, toks = 0.0, 0, 0, 0
     per_kind = {}
-    for k in runner.attn_kinds:
+    for ki, k in enumerate(runner.attn_kinds):
         kd = runner.cfg.kinds[k]
-        layer = 0
-        q = runner.inputs[(k, layer)][0].cpu().double().numpy()
         t_kind, b_kind, n_kind = 0.0, 0, 0
-        for b in range(runner.cfg.batch):
-            if t_used >= budget_s * (runner.attn_kinds.index(k) + 1) / len(runner.attn_kinds):
+        share = budget_s * (ki + 1) / len(runner.attn_kinds)
+        for layer in range(kd.n_layers):
+            q = runner.inputs[(k, layer)][0].cpu().double().numpy()
+            for b in range(runner.cfg.batch):
+                if t_used >= share:
+                    break
+                K, V = runner.gather(k, layer, b)
+                Kd, Vd = K.double().numpy(), V.double().numpy()
+                vis = int(runner.visible_tokens(k)[b])
+                Kd[:, :Kd.shape[1] - vis] = 0.0      # rows outside the window are never read by the oracle
+                Vd[:, :Vd.shape[1] - vis] = 0.0
+                t0 = time.perf_counter()
+                decode_attention_one(q[b], Kd, Vd, runner.scale(k), kd.window)
+                dt = time.perf_counter() - t0
+                t_used += dt
+                t_kind += dt
+                b_kind += vis * kd.bytes_per_token_per_layer
+                n_kind += 1
+            if t_used >= share:
                 break
-            K, V = runner.gather(k, layer, b)
-            Kd, Vd = K.double().numpy(), V.double().numpy()
-            vis = int(runner.visible_tokens(k)[b])
-            Kd[:, :Kd.shape[1] - vis] = 0.0      # rows outside the window are never read by the oracle
-            Vd[:, :Vd.shape[1] - vis] = 0.0
-            t0 = time.perf_counter()
-            decode_attention_one(q[b], Kd, Vd, runner.scale(k), kd.window)
-            dt = time.perf_counter() - t0
-            t_used += dt
-            t_kind += dt
-            b_kind += vis * kd.bytes_per_token_per_layer
-            n_kind += 1
         per_kind[k] = (t_kind, b_kind, n_kind)
         nbytes += b_kind
         n_units += n_kind
@@ -86,8 +89,9 @@ def cpu_baseline(runner, budget_s: float):
             step_s += t_kind * runner.kv_bytes_layer(k) / b_kind * runner.cfg.kinds[k].n_layers
     return {
         "value": round(gbs, 4), "unit": "GB/s", "cores": int(threads), "kind": "oracle",
-        "sample": f"{n_units} (request, layer) slices: layer 0 of each attention kind, requests in batch "
-                  f"order until {budget_s:.0f} s of oracle time; fp64 numpy; scaled to a whole step by "
+        "sample": f"{n_units} (request, layer) slices of the same step, read back from the pool: layers then "
+                  f"requests in order, each attention kind until its share of {budget_s:.0f} s of oracle "
+                  f"time is used; fp64 numpy; scaled to a whole step by bytes and "
                   f"layer count: {step_s:.1f} s/step = {runner.cfg.batch / step_s if step_s else 0:.3f} tokens/s",
         "seconds": round(t_used, 2),
     }
@@ -108,7 +112,7 @@ def main():
 
     _lib.load()     # no library, no benchmark: there is no other path
     cfg = configs.ALL[args.workload]()
-    total_steps = args.steps + args.warmup
+    total_steps = 2 * args.steps + args.warmup
     t_setup = time.perf_counter()
     r = DecodeRunner(cfg, args.seed, pages_per_split=args.pages_per_split, step_budget=total_steps + 2)
     r.build_contexts()
@@ -130,20 +134,13 @@ def main():
         one_step()
     torch.cuda.synchronize()
 
-    use_events = not args.no_kernel_events
-    ev = []
-    if use_events:
-        for _ in range(args.steps):
-            ev.append({key: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-                       for key in r.schedule})
+    # Timed region: exactly `steps` whole steps between two synchronisations -> value.
     step_bytes = []
-    layer_bytes = []
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        one_step(ev[i] if use_events else None)
+        one_step()
         step_bytes.append(r.kv_bytes_step())
-        layer_bytes.append({k: r.kv_bytes_layer(k) for k in r.attn_kinds})
     torch.cuda.synchronize()
     t1 = time.perf_counter()
 
@@ -152,6 +149,24 @@ def main():
     total_bytes = float(sum(step_bytes))
     gbs = total_bytes / elapsed / 1e9
     tokens_per_s = cfg.batch * args.steps / elapsed
+
+    # The same number of steps again, now with a pair of events around every launch of the
+    # dominant kernel (on the stream it is launched on).  Kept out of the region above because
+    # each event record costs a few microseconds between kernels, 84 times per step.
+    use_events = not args.no_kernel_events
+    ev, layer_bytes = [], []
+    ms_per_step_events = None
+    if use_events:
+        for _ in range(args.steps):
+            ev.append({key: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+                       for key in r.schedule})
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        for i in range(args.steps):
+            one_step(ev[i])
+            layer_bytes.append({k: r.kv_bytes_layer(k) for k in r.attn_kinds})
+        torch.cuda.synchronize()
+        ms_per_step_events = (time.perf_counter() - t2) / args.steps * 1e3
 
     roof = {"bound": "hbm", "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": None,
             "traffic": None, "kernel": "decode_partial_kernel"}
@@ -171,6 +186,7 @@ def main():
         roof.update({
             "achieved": round(achieved, 1), "frac": round(achieved / HBM_PEAK_GBS, 4),
             "launches": n_launch, "avg_launch_us": round(k_ms / n_launch * 1e3, 2),
+            "ms_per_step_with_events": round(ms_per_step_events, 3),
             "algorithmic_bytes_per_launch": round(k_bytes / n_launch),
             "per_kind_GBps": {cfg.kinds[k].name: round(per_kind_bytes[k] / (per_kind_ms[k] * 1e-3) / 1e9, 1)
                               for k in r.attn_kinds},

@@ -358,11 +358,19 @@ struct QuadEngine {
       }
     };
 
-    u32x4 kbuf[NLD], vbuf[NLD];
-    load_pages(0, k_voff, 64, kbuf);
+    // Software pipeline, two tiles deep: while tile t is computed, K(t+1), V(t+1) and (after
+    // the scores) K(t+2) are in flight, 16 to 32 KiB per wavefront.  Loads return in order,
+    // so waiting for the oldest tile leaves the younger ones outstanding.
+    u32x4 kb[2][NLD], vb[2][NLD];
+    load_pages(0, k_voff, 64, kb[0]);
+    load_pages(0, v_voff, 1024, vb[0]);
+    if (n_tiles > 1) {
+      load_pages(1, k_voff, 64, kb[1]);
+      ids.k_stream_at(PPT);
+    }
 
-    for (int tile = 0; tile < n_tiles; ++tile) {
-      load_pages(tile, v_voff, 1024, vbuf);
+    auto step = [&](int tile, u32x4* kbuf, u32x4* vbuf, u32x4* v_next) {
+      if (tile + 1 < n_tiles) load_pages(tile + 1, v_voff, 1024, v_next);
 
       // one score per (page of the tile, query head) and lane: token k_tok of that page
       float s[PPT][G];
@@ -378,9 +386,9 @@ struct QuadEngine {
           s[pp][g] = x * p.scale_log2;
         }
 
-      if (tile + 1 < n_tiles) {
-        load_pages(tile + 1, k_voff, 64, kbuf);
-        ids.k_stream_at((tile + 1) * PPT);
+      if (tile + 2 < n_tiles) {
+        load_pages(tile + 2, k_voff, 64, kbuf);
+        ids.k_stream_at((tile + 2) * PPT);
       }
 
       const int tile_tok = tok0 + tile * PPT * T;           // first token of the tile
@@ -439,6 +447,11 @@ struct QuadEngine {
           for (int j = 0; j < EPL; ++j) acc[g][j] = fmaf(w[g], vf[j], acc[g][j]);
       }
       __builtin_amdgcn_wave_barrier();
+    };
+
+    for (int tile = 0; tile < n_tiles; tile += 2) {
+      step(tile, kb[0], vb[0], vb[1]);
+      if (tile + 1 < n_tiles) step(tile + 1, kb[1], vb[1], vb[0]);
     }
 
     // every quad of lanes carried the same l; the V lane groups share m, so they just add up
@@ -798,8 +811,8 @@ DecodeFn pick_d(int D, bool quad, int G) {
   }
 }
 
-// Blocks of `fn` that can be resident on the device at once (a multiple of 8, one share per
-// XCD), capped at kMaxPartitions.  Cached per kernel; 2048 when no device can be asked.
+// Partitions of the automatic mode: resident blocks of `fn`, at most one per SIMD, a multiple
+// of 8 (one share per XCD), capped at kMaxPartitions.  Cached per kernel; 2048 when no device can be asked.
 int resident_partitions(DecodeFn fn) {
   static std::mutex mu;
   static std::unordered_map<const void*, int> cache;
@@ -812,7 +825,9 @@ int resident_partitions(DecodeFn fn) {
       hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess &&
       hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kWave, 0) == hipSuccess &&
       cus > 0 && per_cu > 0) {
-    n = std::min(kMaxPartitions, cus * per_cu) / 8 * 8;
+    // one wavefront per SIMD (4 per compute unit): measured faster than filling every slot,
+    // and it leaves each wavefront the registers for a deep load pipeline
+    n = std::min(kMaxPartitions, cus * std::min(per_cu, 4)) / 8 * 8;
     n = std::max(n, 8);
     cache.emplace(reinterpret_cast<const void*>(fn), n);
   } else {
