@@ -121,6 +121,23 @@ def test_all_built_shapes_full_attention(dtype, D, G):
     r.close()
 
 
+@pytest.mark.parametrize("T,dtype,D,G,window", [
+    (8, "bf16", 128, 2, 0), (8, "f32", 64, 4, 0), (32, "bf16", 256, 2, 0), (32, "bf16", 64, 1, 50),
+    (64, "bf16", 128, 4, 0), (64, "f32", 128, 2, 70), (128, "bf16", 64, 2, 0), (128, "f32", 256, 1, 300),
+    (8, "f32", 256, 2, 9)])
+def test_other_page_sizes(T, dtype, D, G, window):
+    """Pages of 8, 32, 64 and 128 tokens go through the general (row) engine."""
+    print(f"[case] T={T} {dtype} D={D} G={G} W={window}", flush=True)
+    cfg = custom_cfg(dtype, D, 2 * G, 2, WINDOW if window else FULL, window=window, hi=900, T=T)
+    for pps in (0, 2):
+        r = _runner(cfg, 40 + T + D, pages_per_split=pps)
+        prepare(r)
+        r.device_step()
+        check_against_oracle(r, f"{cfg.name}/T{T}/pps{pps}")
+        check_append_landed(r)
+        r.close()
+
+
 @pytest.mark.parametrize("dtype,D,G,W", [("bf16", 256, 2, 100), ("bf16", 128, 4, 64), ("bf16", 64, 1, 33),
                                          ("f32", 128, 2, 32), ("f32", 64, 4, 17), ("bf16", 128, 8, 1),
                                          ("f32", 256, 1, 500), ("bf16", 256, 2, 16)])
