@@ -39,6 +39,9 @@ def parse():
                     help="do not bracket the decode kernel with events (roofline.achieved becomes null)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle timing")
+    ap.add_argument("--copy-calibration", type=float, default=0.0, metavar="GiB",
+                    help="instead of the benchmark, run the library's plain copy and read kernels over "
+                         "a buffer of this size (to calibrate profiler byte counters) and exit")
     return ap.parse_args()
 
 
@@ -97,6 +100,30 @@ def cpu_baseline(runner, budget_s: float):
     }
 
 
+def copy_calibration(gib: float):
+    """Known traffic for counter calibration: copy reads N and writes N bytes, read reads N."""
+    import torch
+    import paper_2503_18292_amd as J
+    n = int(gib * 2**30) // 4096 * 4096
+    src = torch.empty(n, dtype=torch.uint8, device="cuda")
+    src.fill_(1)
+    dst = torch.empty_like(src)
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    out = {"bytes": n}
+    for name, fn, moved in (("copy", lambda: J.stream_copy(dst, src, n), 2 * n),
+                            ("read", lambda: J.stream_read(src, n, sink), n)):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(5):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        out[name + "_GBps"] = round(moved / (e0.elapsed_time(e1) / 5 * 1e-3) / 1e9, 1)
+    print(json.dumps({"copy_calibration": out}), flush=True)
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -111,6 +138,8 @@ def main():
     from workloads import configs
 
     _lib.load()     # no library, no benchmark: there is no other path
+    if args.copy_calibration > 0:
+        return copy_calibration(args.copy_calibration)
     cfg = configs.ALL[args.workload]()
     total_steps = 2 * args.steps + args.warmup
     t_setup = time.perf_counter()
