@@ -24,6 +24,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
+# HBM traffic of one decode_partial launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
+# each scaled by what the same counter reads for a plain copy of known size (summary and
+# commands: profiles/decode_kernels_gemma2_9b_hbm_traffic.md): fetched bytes are 1.007 x the
+# algorithmic K/V bytes, written bytes 3.18e6 per launch.  Only known for the default workload.
+MEASURED_TRAFFIC = {"gemma2_9b": {"fetch_over_algorithmic": 1.007, "write_bytes": 3.18e6}}
 
 
 def parse():
@@ -217,6 +222,9 @@ def main():
             "launches": n_launch, "avg_launch_us": round(k_ms / n_launch * 1e3, 2),
             "ms_per_step_with_events": round(ms_per_step_events, 3),
             "algorithmic_bytes_per_launch": round(k_bytes / n_launch),
+            "traffic": (round(MEASURED_TRAFFIC[cfg.name]["fetch_over_algorithmic"] * k_bytes / n_launch
+                              + MEASURED_TRAFFIC[cfg.name]["write_bytes"])
+                        if cfg.name in MEASURED_TRAFFIC and args.pages_per_split == 0 else None),
             "per_kind_GBps": {cfg.kinds[k].name: round(per_kind_bytes[k] / (per_kind_ms[k] * 1e-3) / 1e9, 1)
                               for k in r.attn_kinds},
         })
