@@ -186,6 +186,20 @@ int jenga_kv_append(const jenga_pool* pool, int32_t kind, int32_t layer,
                     const int32_t* block_table, int32_t bt_stride,
                     const int32_t* seq_lens, int32_t batch, jenga_stream stream);
 
+/* Bulk form of jenga_kv_append for a run of tokens per request (the write a chunked prefill
+ * does just before decoding starts, Sec. 6.2): request b owns source rows
+ * [cu_tokens[b], cu_tokens[b+1]) and its first row is the token at sequence position
+ * start_pos[b]; row r of k_src / v_src is [n_kv_heads][head_dim] in the kind's dtype.  Tokens
+ * whose page is not resident (negative table entry, e.g. a window page that already slid out)
+ * are skipped.  k_src, v_src: device, [total_tokens][n_kv_heads][head_dim], 16-byte aligned;
+ * cu_tokens: device int32 [batch + 1], non-decreasing, cu_tokens[batch] <= total_tokens;
+ * start_pos: device int32 [batch]; block_table as for jenga_kv_append.  Works for FULL, WINDOW
+ * and CROSS kinds (encoder K/V is written once this way).  Errors as jenga_kv_append. */
+int jenga_kv_write_range(const jenga_pool* pool, int32_t kind, int32_t layer,
+                         const void* k_src, const void* v_src, const int32_t* cu_tokens,
+                         const int32_t* start_pos, const int32_t* block_table, int32_t bt_stride,
+                         int32_t batch, int32_t total_tokens, jenga_stream stream);
+
 /* Upper bound of the number of work partitions (wavefront tasks) the decode kernels use for
  * these arguments.  The visible K/V of all (request, KV head) pairs, cut into tiles and laid
  * end to end, is divided into equal partitions; pages_per_split = 0 lets the library take one

@@ -53,6 +53,7 @@ SIGNATURES = {
     "jenga_requests_extend": (C.c_int, [c_vp, c_i32, c_vp, c_vp, c_i32]),
     "jenga_block_table_fill": (C.c_int, [c_vp, c_i32, c_vp, c_i32, c_vp, c_i32]),
     "jenga_kv_append": (C.c_int, [c_vp, c_i32, c_i32, c_vp, c_vp, c_vp, c_i32, c_vp, c_i32, c_vp]),
+    "jenga_kv_write_range": (C.c_int, [c_vp, c_i32, c_i32, c_vp, c_vp, c_vp, c_vp, c_vp, c_i32, c_i32, c_i32, c_vp]),
     "jenga_decode_num_partitions": (C.c_int, [c_vp, c_i32, c_i32, c_i32, c_i32, c_i32, c_i32]),
     "jenga_decode_workspace_bytes": (c_i64, [c_vp, c_i32, c_i32, c_i32, c_i32, c_i32, c_i32]),
     "jenga_paged_decode": (C.c_int, [c_vp, c_i32, c_i32, c_vp, c_i32, c_vp, c_i32, c_vp, c_i32,

@@ -199,6 +199,12 @@ class Pool:
                                          _ptr(block_table), block_table.shape[1], _ptr(seq_lens),
                                          seq_lens.shape[0], _stream()), "jenga_kv_append")
 
+    def kv_write_range(self, kind: int, layer: int, k_src, v_src, cu_tokens, start_pos, block_table) -> None:
+        _check(self._lib.jenga_kv_write_range(self._h, kind, layer, _ptr(k_src), _ptr(v_src),
+                                              _ptr(cu_tokens), _ptr(start_pos), _ptr(block_table),
+                                              block_table.shape[1], start_pos.shape[0], k_src.shape[0],
+                                              _stream()), "jenga_kv_write_range")
+
     def decode_num_partitions(self, kind: int, n_q_heads: int, batch: int, max_seq_len: int,
                               window: int = 0, pages_per_split: int = 0) -> int:
         return _check(self._lib.jenga_decode_num_partitions(self._h, kind, n_q_heads, batch, max_seq_len,

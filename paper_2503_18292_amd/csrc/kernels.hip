@@ -1,6 +1,7 @@
 // Device half of the library, written for gfx950 (CDNA4, 64-wide wavefronts).
 //
 //   kv_append_kernel       stores the new token's K/V rows into their page
+//   kv_write_range_kernel  stores a run of tokens per request (chunked prefill) the same way
 //   decode_partial_kernel  streams K and V pages through a layer type's block table with
 //                          16-byte non-temporal loads, fp32 online softmax, the G query heads
 //                          of a KV head share every load; one wavefront per work partition
@@ -755,6 +756,43 @@ __global__ __launch_bounds__(256) void kv_append_kernel(
   *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
 }
 
+// Bulk write of a run of tokens per request (chunked prefill): one thread per 16 bytes.
+// Source rows are token-major, [token][kv head][D]; request b owns rows
+// [cu_tokens[b], cu_tokens[b+1]) and its first row is sequence position start_pos[b].
+__global__ __launch_bounds__(256) void kv_write_range_kernel(
+    char* __restrict__ layer_base, int64_t small_bytes, int32_t head_stride, int32_t v_offset,
+    int32_t t_log2, int32_t n_kv_heads, int32_t row_bytes, const char* __restrict__ k_src,
+    const char* __restrict__ v_src, const int32_t* __restrict__ cu_tokens,
+    const int32_t* __restrict__ start_pos, const int32_t* __restrict__ block_table,
+    int32_t bt_stride, int32_t batch, int64_t total_chunks) {
+  const int chunks = row_bytes / 16;
+  const int64_t idx = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
+  if (idx >= total_chunks) return;
+  const int c = int(idx % chunks);
+  int64_t r = idx / chunks;
+  const int is_v = int(r & 1);
+  r >>= 1;
+  const int h = int(r % n_kv_heads);
+  const int tok = int(r / n_kv_heads);
+  // request of this token: last b with cu_tokens[b] <= tok
+  int lo = 0, hi = batch;
+  while (hi - lo > 1) {
+    const int mid = (lo + hi) >> 1;
+    if (cu_tokens[mid] <= tok) lo = mid; else hi = mid;
+  }
+  const int b = lo;
+  if (tok >= cu_tokens[b + 1]) return;            // padding rows past the last request
+  const int pos = start_pos[b] + (tok - cu_tokens[b]);
+  const int page = pos >> t_log2;
+  if (pos < 0 || page >= bt_stride) return;
+  const int sid = block_table[int64_t(b) * bt_stride + page];
+  if (sid < 0) return;                            // page not resident (e.g. already slid out)
+  const char* src = (is_v ? v_src : k_src) + (int64_t(tok) * n_kv_heads + h) * row_bytes + c * 16;
+  char* dst = layer_base + int64_t(sid) * small_bytes + int64_t(h) * head_stride +
+              (is_v ? v_offset : 0) + (pos & ((1 << t_log2) - 1)) * row_bytes + c * 16;
+  *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
+}
+
 __global__ __launch_bounds__(256) void stream_copy_kernel(u32x4* __restrict__ dst,
                                                           const u32x4* __restrict__ src, int64_t n) {
   const int64_t stride = int64_t(gridDim.x) * blockDim.x;
@@ -934,6 +972,31 @@ int jenga_kv_append(const jenga_pool* pool, int32_t kind, int32_t layer, const v
                      int32_t(k.desc.tokens_per_page * row_bytes), k.t_log2, k.desc.n_kv_heads,
                      row_bytes, static_cast<const char*>(k_new), static_cast<const char*>(v_new),
                      block_table, bt_stride, seq_lens, batch);
+  return hip_status();
+}
+
+int jenga_kv_write_range(const jenga_pool* pool, int32_t kind, int32_t layer, const void* k_src,
+                         const void* v_src, const int32_t* cu_tokens, const int32_t* start_pos,
+                         const int32_t* block_table, int32_t bt_stride, int32_t batch,
+                         int32_t total_tokens, jenga_stream stream) {
+  if (!pool || kind < 0 || kind >= int32_t(pool->kinds.size())) return JENGA_ERR_INVALID;
+  const jenga::Kind& k = pool->kinds[kind];
+  if (!attention_kind(k)) return JENGA_ERR_INVALID;
+  if (!pool->base || layer < 0 || layer >= k.desc.n_layers || !k_src || !v_src || !cu_tokens ||
+      !start_pos || !block_table || batch < 0 || total_tokens < 0 || bt_stride < 1)
+    return JENGA_ERR_INVALID;
+  if (!aligned16(k_src) || !aligned16(v_src)) return JENGA_ERR_ALIGN;
+  if (batch == 0 || total_tokens == 0) return JENGA_OK;
+  const int row_bytes = k.desc.head_dim * k.elem_bytes;
+  const int64_t total_chunks = int64_t(total_tokens) * k.desc.n_kv_heads * 2 * (row_bytes / 16);
+  const int64_t blocks = (total_chunks + 255) / 256;
+  if (blocks > 0x7fffffff) return JENGA_ERR_UNSUPPORTED;
+  hipLaunchKernelGGL(kv_write_range_kernel, dim3(unsigned(blocks)), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), pool->base + int64_t(layer) * k.slice_bytes,
+                     k.small_bytes, int32_t(2 * k.desc.tokens_per_page * row_bytes),
+                     int32_t(k.desc.tokens_per_page * row_bytes), k.t_log2, k.desc.n_kv_heads,
+                     row_bytes, static_cast<const char*>(k_src), static_cast<const char*>(v_src),
+                     cu_tokens, start_pos, block_table, bt_stride, batch, total_chunks);
   return hip_status();
 }
 
