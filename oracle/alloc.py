@@ -277,3 +277,202 @@ class OracleRequests:
         if len(lst) > width:
             raise InvalidOp("row wider than the table")
         return lst + [-1] * (width - len(lst))
+
+
+# ---------------------------------------------------------------------------
+# Sec. 5: page states, LRU keys and the five-step allocation of Sec. 5.4
+# ---------------------------------------------------------------------------
+EMPTY, EVICTABLE, USED = 0, 1, 2
+
+
+class OracleCachingPool(OraclePool):
+    """The allocator with prefix-cache page states (Sec. 5.4) and LRU eviction (Sec. 5.1).
+
+    A small page is empty (no valid KV), evictable (valid KV, used by no request) or used.
+    release(keep_cached=True) leaves a page evictable instead of empty; acquire() takes an
+    evictable page back into use (a prefix-cache hit).  Allocation follows the five steps of
+    Sec. 5.4; with no evictable page anywhere they reduce to the three steps of Sec. 4.3.
+
+    LRU keys per small page: last_access (Sec. 5.1 update_last_access) and prefix_length
+    (Sec. 5.1 set_prefix_length).  The page with the earliest last access goes first; among
+    equal times the one with the largest prefix length (Sec. 5.1: "the token with the highest
+    length is evicted before other tokens").
+
+    Readings where the paper is silent:
+      * a large page counts as evictable when none of its small pages is used and at least
+        one is evictable (the paper says "all its small pages are evictable"; a large page
+        holding a mix of empty and evictable pages would otherwise be out of reach of step 3
+        although evicting it costs less);
+      * its LRU time is the latest last access among its evictable small pages (Sec. 5.4),
+        ties go to the larger maximum prefix length, then to the lower page number;
+      * remaining ties between small pages go to the lower id.
+    """
+
+    def __init__(self, *args, **kwargs):
+        super().__init__(*args, **kwargs)
+        self.cached = [np.zeros(self.n_large * rk, dtype=bool) for rk in self.r]
+        self.last_access = [np.zeros(self.n_large * rk, dtype=np.int64) for rk in self.r]
+        self.prefix_length = [np.zeros(self.n_large * rk, dtype=np.int64) for rk in self.r]
+
+    # ---- states -----------------------------------------------------------
+    def state(self, k: int, sid: int) -> int:
+        if self.refcount[k][sid] > 0:
+            return USED
+        return EVICTABLE if self.cached[k][sid] else EMPTY
+
+    def _empty_mask(self, k: int) -> np.ndarray:
+        return (self.refcount[k] == 0) & ~self.cached[k]
+
+    def _larges_with_empty(self, k: int, mask: np.ndarray) -> np.ndarray:
+        has = self._empty_mask(k).reshape(self.n_large, self.r[k]).any(axis=1)
+        return np.flatnonzero(mask & (self.large_kind == k) & has)
+
+    def _take_lowest_empty(self, k: int, large: int) -> int:
+        rk = self.r[k]
+        slot = int(np.flatnonzero(self._empty_mask(k)[large * rk:(large + 1) * rk])[0])
+        sid = large * rk + slot
+        self.refcount[k][sid] = 1
+        return sid
+
+    def set_last_access(self, k: int, sid: int, time: int) -> None:
+        self._check_kind(k)
+        if self.state(k, sid) == EMPTY:
+            raise InvalidOp("empty page has no access time")
+        self.last_access[k][sid] = time
+
+    def set_prefix_length(self, k: int, sid: int, length: int) -> None:
+        self._check_kind(k)
+        if self.state(k, sid) == EMPTY:
+            raise InvalidOp("empty page has no prefix length")
+        self.prefix_length[k][sid] = length
+
+    def release(self, k: int, sid: int, keep_cached: bool) -> None:
+        """One reference fewer; at zero the page becomes evictable (keep_cached) or empty."""
+        self._check_kind(k)
+        if not (0 <= sid < self.refcount[k].size) or self.refcount[k][sid] == 0:
+            raise InvalidOp("release of a page that is not in use")
+        self.refcount[k][sid] -= 1
+        if self.refcount[k][sid] == 0:
+            self.cached[k][sid] = bool(keep_cached)
+            self._return_large_if_empty(k, sid // self.r[k])
+
+    def free(self, k: int, sid: int) -> None:      # Sec. 4.1 free(): no caching
+        self.release(k, sid, keep_cached=False)
+
+    def acquire(self, k: int, sid: int) -> None:
+        """Prefix-cache hit: an evictable page is used again."""
+        self._check_kind(k)
+        if not (0 <= sid < self.refcount[k].size) or self.state(k, sid) != EVICTABLE:
+            raise InvalidOp("acquire of a page that is not evictable")
+        self.cached[k][sid] = False
+        self.refcount[k][sid] = 1
+
+    def _return_large_if_empty(self, k: int, large: int) -> None:
+        rk = self.r[k]
+        sl = slice(large * rk, (large + 1) * rk)
+        if not self.refcount[k][sl].any() and not self.cached[k][sl].any():
+            self.large_kind[large] = -1
+            self.large_req[large] = 0
+
+    # ---- Sec. 5.4: the five steps -------------------------------------------
+    def alloc_evict(self, k: int, request: int):
+        """Returns (small id, [(kind, id) of every page evicted to make room])."""
+        self._check_kind(k)
+        # 1. an empty small page associated with this request
+        mine = self._larges_with_empty(k, self.large_req == request)
+        if mine.size:
+            return self._take_lowest_empty(k, int(mine[0])), []
+        # 2. an empty large page
+        free_large = np.flatnonzero(self.large_kind == -1)
+        if free_large.size:
+            large = int(free_large[0])
+            self.large_kind[large] = k
+            self.large_req[large] = request
+            return self._take_lowest_empty(k, large), []
+        # 3. evict an evictable large page, least recently used first
+        best, best_key = None, None
+        for large in range(self.n_large):
+            ko = int(self.large_kind[large])
+            if ko < 0:
+                continue
+            rk = self.r[ko]
+            ids = np.arange(large * rk, (large + 1) * rk)
+            if (self.refcount[ko][ids] > 0).any() or not self.cached[ko][ids].any():
+                continue
+            c = ids[self.cached[ko][ids]]
+            key = (int(self.last_access[ko][c].max()), -int(self.prefix_length[ko][c].max()), large)
+            if best_key is None or key < best_key:
+                best, best_key = large, key
+        if best is not None:
+            ko = int(self.large_kind[best])
+            rk = self.r[ko]
+            evicted = [(ko, int(s)) for s in range(best * rk, (best + 1) * rk) if self.cached[ko][s]]
+            for _, s in evicted:
+                self.cached[ko][s] = False
+            self.large_kind[best] = k            # all its small pages are empty now: re-typed
+            self.large_req[best] = request
+            return self._take_lowest_empty(k, best), evicted
+        # 4. an empty small page of this kind associated with another request
+        anyone = self._larges_with_empty(k, np.ones(self.n_large, dtype=bool))
+        if anyone.size:
+            return self._take_lowest_empty(k, int(anyone[0])), []
+        # 5. evict an evictable small page of this kind, least recently used first
+        cand = np.flatnonzero(self.cached[k] & (self.refcount[k] == 0))
+        if cand.size:
+            keys = [(int(self.last_access[k][s]), -int(self.prefix_length[k][s]), int(s)) for s in cand]
+            sid = min(keys)[2]
+            self.cached[k][sid] = False
+            self.refcount[k][sid] = 1
+            return sid, [(k, sid)]
+        raise OutOfPages(f"kind {k}")
+
+    def alloc(self, k: int, request: int) -> int:
+        return self.alloc_evict(k, request)[0]
+
+    def evictable_small(self, k: int) -> int:
+        return int((self.cached[k] & (self.refcount[k] == 0)).sum())
+
+    def live_extents(self):
+        out = super().live_extents()
+        for k in range(len(self.S)):
+            for sid in np.flatnonzero(self.cached[k] & (self.refcount[k] == 0)):
+                b = int(sid) * self.S[k]
+                out.append((b, b + self.S[k], k, int(sid)))
+        return out
+
+
+# ---------------------------------------------------------------------------
+# Sec. 5.2 / 5.3: customised hit rules
+# ---------------------------------------------------------------------------
+def possible_prefixes_full(is_hit: Sequence[bool]) -> List[int]:
+    """Full attention: a prefix is valid when every token in it is cached (Sec. 5.2)."""
+    out = []
+    for p in range(1, len(is_hit) + 1):
+        if not is_hit[p - 1]:
+            break
+        out.append(p)
+    return out
+
+
+def possible_prefixes_window(is_hit: Sequence[bool], window: int) -> List[int]:
+    """Sliding window: prefix p is valid when its last `window` tokens are cached
+    (Fig. interface/sliding: all x in [0, sliding) with is_hit[p - x], token indices from 1)."""
+    out = []
+    for p in range(1, len(is_hit) + 1):
+        if all(is_hit[p - x - 1] for x in range(window) if p - x >= 1):
+            out.append(p)
+    return out
+
+
+def possible_prefixes_every(is_hit: Sequence[bool], stride: int) -> List[int]:
+    """State-space layers cache one state every `stride` tokens (512 in Sec. 5.3): prefix p
+    is valid when p is a multiple of the stride and the state after token p is cached."""
+    return [p for p in range(stride, len(is_hit) + 1, stride) if is_hit[p - 1]]
+
+
+def longest_common_prefix(valid_sets: Sequence[Sequence[int]]) -> int:
+    """Sec. 5.2: the longest prefix valid for every layer type (0 when there is none)."""
+    common = set(valid_sets[0])
+    for v in valid_sets[1:]:
+        common &= set(v)
+    return max(common) if common else 0
