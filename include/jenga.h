@@ -95,8 +95,14 @@ typedef struct {
   int64_t small_per_large;    /* r_k = large_page_bytes / small_page_bytes */
   int64_t owned_large_pages;  /* large pages currently split into pages of this kind */
   int64_t used_small_pages;   /* reference count > 0 */
-  int64_t unused_small_pages; /* inside owned large pages: internal fragmentation (Sec. 4.3, 4.4) */
+  int64_t unused_small_pages; /* empty ones inside owned large pages: internal fragmentation (Sec. 4.3, 4.4) */
+  int64_t evictable_small_pages; /* valid contents, no user (Sec. 5.4) */
 } jenga_kind_stats;
+
+/* State of a small page under prefix caching (Sec. 5.4). */
+typedef enum { JENGA_PAGE_EMPTY = 0, JENGA_PAGE_EVICTABLE = 1, JENGA_PAGE_USED = 2 } jenga_page_state;
+/* Customised hit rules of Sec. 5.2 / 5.3. */
+typedef enum { JENGA_HIT_FULL = 0, JENGA_HIT_WINDOW = 1, JENGA_HIT_EVERY = 2 } jenga_hit_rule;
 
 /* ------------------------------------------------------------------ host: pool */
 
@@ -171,6 +177,51 @@ int jenga_requests_extend(jenga_pool* pool, int32_t kind, const int64_t* request
                           const int64_t* new_lens, int32_t n);
 int jenga_block_table_fill(const jenga_pool* pool, int32_t kind, const int64_t* requests, int32_t n,
                            int32_t* table, int32_t width);
+
+/* ------------------------------------------------- host: prefix-cache side (paper Sec. 5) */
+
+/* jenga_alloc_small is the five-step allocation of Sec. 5.4:
+ *   1. an empty small page associated with the request;  2. an empty large page;
+ *   3. evict the least recently used evictable large page (of any kind; it is re-typed);
+ *   4. an empty small page of the kind associated with another request;
+ *   5. evict the least recently used evictable small page of the kind.
+ * With nothing evictable this is the three-step order of Sec. 4.3.  A large page is evictable
+ * when none of its small pages is used and at least one is evictable; its LRU time is the
+ * latest last access among its evictable pages.  Among equal times the larger prefix length
+ * goes first (Sec. 5.1), then the lower number.  This variant also reports what was evicted,
+ * so the caller can drop it from its prefix index: up to `capacity` (kind, id) pairs are
+ * written to the host arrays (either may be NULL), *out_n_evicted gets the full count. */
+int jenga_alloc_small_evict(jenga_pool* pool, int32_t kind, int64_t request, int32_t* out_small_id,
+                            int32_t* evicted_kinds, int32_t* evicted_ids, int32_t capacity,
+                            int32_t* out_n_evicted);
+/* Like jenga_free_small, but at reference count zero the page stays evictable (valid contents
+ * kept for later prefix hits) when keep_cached != 0. */
+int jenga_release_small(jenga_pool* pool, int32_t kind, int32_t small_id, int32_t keep_cached);
+/* Prefix-cache hit: an evictable page is used again (reference count 1).  INVALID otherwise. */
+int jenga_acquire_cached(jenga_pool* pool, int32_t kind, int32_t small_id);
+/* LRU keys of Sec. 5.1 (update_last_access, set_prefix_length) for a used or evictable page. */
+int jenga_set_last_access(jenga_pool* pool, int32_t kind, int32_t small_id, int64_t time);
+int jenga_set_prefix_length(jenga_pool* pool, int32_t kind, int32_t small_id, int64_t length);
+int jenga_small_state(const jenga_pool* pool, int32_t kind, int32_t small_id, int32_t* out_state);
+/* Request-level forms: release every page of the request (evictable if keep_cached); stamp
+ * the pages covering tokens [first_token, end_token) of one kind with `time` (the layer type
+ * decides the range: everything for full attention, the window for sliding-window layers,
+ * Sec. 5.1); give page p of the request prefix length (p + 1) * tokens_per_page. */
+int jenga_request_release(jenga_pool* pool, int64_t request, int32_t keep_cached);
+int jenga_request_touch(jenga_pool* pool, int64_t request, int32_t kind, int64_t first_token,
+                        int64_t end_token, int64_t time);
+int jenga_request_set_prefix_lengths(jenga_pool* pool, int64_t request, int32_t kind);
+
+/* get_possible_prefix of Sec. 5.2: is_hit[t] != 0 when token t (0-based) is cached for the
+ * layer type; out_valid (host, n_tokens + 1 bytes) gets out_valid[p] = 1 when the prefix of p
+ * tokens is a valid hit.  JENGA_HIT_FULL: all p tokens cached.  JENGA_HIT_WINDOW: the last
+ * min(param, p) tokens cached.  JENGA_HIT_EVERY: p is a multiple of param and token p - 1 is
+ * cached (state-space layers cache one state every 512 tokens, Sec. 5.3). */
+int jenga_possible_prefixes(int32_t rule, int32_t param, const uint8_t* is_hit, int32_t n_tokens,
+                            uint8_t* out_valid);
+/* Longest prefix valid for every layer type (Sec. 5.2): valid_sets[s] as written by
+ * jenga_possible_prefixes.  Returns the length (0: none) or a negative status. */
+int jenga_longest_common_prefix(const uint8_t* const* valid_sets, int32_t n_sets, int32_t n_tokens);
 
 /* ------------------------------------------------------------------------ device: kernels */
 

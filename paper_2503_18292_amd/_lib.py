@@ -29,7 +29,7 @@ class PoolInfo(C.Structure):
 class KindStats(C.Structure):
     _fields_ = [("small_page_bytes", c_i64), ("slice_bytes", c_i64), ("small_per_large", c_i64),
                 ("owned_large_pages", c_i64), ("used_small_pages", c_i64),
-                ("unused_small_pages", c_i64)]
+                ("unused_small_pages", c_i64), ("evictable_small_pages", c_i64)]
 
 
 # name -> (restype, argtypes); mirrors include/jenga.h one to one
@@ -52,6 +52,17 @@ SIGNATURES = {
     "jenga_request_block_table_row": (C.c_int, [c_vp, c_i64, c_i32, p_i32, c_i32]),
     "jenga_requests_extend": (C.c_int, [c_vp, c_i32, c_vp, c_vp, c_i32]),
     "jenga_block_table_fill": (C.c_int, [c_vp, c_i32, c_vp, c_i32, c_vp, c_i32]),
+    "jenga_alloc_small_evict": (C.c_int, [c_vp, c_i32, c_i64, p_i32, p_i32, p_i32, c_i32, p_i32]),
+    "jenga_release_small": (C.c_int, [c_vp, c_i32, c_i32, c_i32]),
+    "jenga_acquire_cached": (C.c_int, [c_vp, c_i32, c_i32]),
+    "jenga_set_last_access": (C.c_int, [c_vp, c_i32, c_i32, c_i64]),
+    "jenga_set_prefix_length": (C.c_int, [c_vp, c_i32, c_i32, c_i64]),
+    "jenga_small_state": (C.c_int, [c_vp, c_i32, c_i32, p_i32]),
+    "jenga_request_release": (C.c_int, [c_vp, c_i64, c_i32]),
+    "jenga_request_touch": (C.c_int, [c_vp, c_i64, c_i32, c_i64, c_i64, c_i64]),
+    "jenga_request_set_prefix_lengths": (C.c_int, [c_vp, c_i64, c_i32]),
+    "jenga_possible_prefixes": (C.c_int, [c_i32, c_i32, c_vp, c_i32, c_vp]),
+    "jenga_longest_common_prefix": (C.c_int, [c_vp, c_i32, c_i32]),
     "jenga_kv_append": (C.c_int, [c_vp, c_i32, c_i32, c_vp, c_vp, c_vp, c_i32, c_vp, c_i32, c_vp]),
     "jenga_kv_write_range": (C.c_int, [c_vp, c_i32, c_i32, c_vp, c_vp, c_vp, c_vp, c_vp, c_i32, c_i32, c_i32, c_vp]),
     "jenga_decode_num_partitions": (C.c_int, [c_vp, c_i32, c_i32, c_i32, c_i32, c_i32, c_i32]),

@@ -64,6 +64,31 @@ def lcm_page_bytes(kinds: Sequence[KindDesc]) -> int:
     return out.value
 
 
+def possible_prefixes(rule: int, param: int, is_hit) -> list:
+    """Valid prefix lengths for one layer type (jenga_possible_prefixes)."""
+    n = len(is_hit)
+    hit = (C.c_uint8 * max(n, 1))(*[1 if h else 0 for h in is_hit])
+    out = (C.c_uint8 * (n + 1))()
+    _check(_lib.load().jenga_possible_prefixes(rule, param, hit, n, out), "jenga_possible_prefixes")
+    return [p for p in range(1, n + 1) if out[p]]
+
+
+def longest_common_prefix(valid_sets, n_tokens: int) -> int:
+    arrs = []
+    for v in valid_sets:
+        a = (C.c_uint8 * (n_tokens + 1))()
+        for p in v:
+            a[p] = 1
+        arrs.append(a)
+    ptrs = (C.c_void_p * len(arrs))(*[C.cast(a, C.c_void_p) for a in arrs])
+    return _check(_lib.load().jenga_longest_common_prefix(ptrs, len(arrs), n_tokens),
+                  "jenga_longest_common_prefix")
+
+
+HIT_FULL, HIT_WINDOW, HIT_EVERY = 0, 1, 2
+PAGE_EMPTY, PAGE_EVICTABLE, PAGE_USED = 0, 1, 2
+
+
 def version() -> int:
     return _lib.load().jenga_version()
 
@@ -113,6 +138,43 @@ class Pool:
 
     def free_small(self, kind: int, small_id: int) -> None:
         _check(self._lib.jenga_free_small(self._h, kind, small_id), "jenga_free_small")
+
+    # ---- host: prefix-cache side ----------------------------------------------------
+    def alloc_small_evict(self, kind: int, request: int, capacity: int = 256):
+        """Returns (small id, [(kind, id) of every page evicted to make room])."""
+        out, n = C.c_int32(-1), C.c_int32(0)
+        ks, ids = (C.c_int32 * capacity)(), (C.c_int32 * capacity)()
+        _check(self._lib.jenga_alloc_small_evict(self._h, kind, request, C.byref(out), ks, ids, capacity,
+                                                 C.byref(n)), "jenga_alloc_small_evict")
+        return out.value, [(ks[i], ids[i]) for i in range(min(n.value, capacity))]
+
+    def release_small(self, kind: int, small_id: int, keep_cached: bool) -> None:
+        _check(self._lib.jenga_release_small(self._h, kind, small_id, int(keep_cached)), "jenga_release_small")
+
+    def acquire_cached(self, kind: int, small_id: int) -> None:
+        _check(self._lib.jenga_acquire_cached(self._h, kind, small_id), "jenga_acquire_cached")
+
+    def set_last_access(self, kind: int, small_id: int, time: int) -> None:
+        _check(self._lib.jenga_set_last_access(self._h, kind, small_id, time), "jenga_set_last_access")
+
+    def set_prefix_length(self, kind: int, small_id: int, length: int) -> None:
+        _check(self._lib.jenga_set_prefix_length(self._h, kind, small_id, length), "jenga_set_prefix_length")
+
+    def small_state(self, kind: int, small_id: int) -> int:
+        out = C.c_int32(0)
+        _check(self._lib.jenga_small_state(self._h, kind, small_id, C.byref(out)), "jenga_small_state")
+        return out.value
+
+    def request_release(self, request: int, keep_cached: bool) -> None:
+        _check(self._lib.jenga_request_release(self._h, request, int(keep_cached)), "jenga_request_release")
+
+    def request_touch(self, request: int, kind: int, first_token: int, end_token: int, time: int) -> None:
+        _check(self._lib.jenga_request_touch(self._h, request, kind, first_token, end_token, time),
+               "jenga_request_touch")
+
+    def request_set_prefix_lengths(self, request: int, kind: int) -> None:
+        _check(self._lib.jenga_request_set_prefix_lengths(self._h, request, kind),
+               "jenga_request_set_prefix_lengths")
 
     def get_info(self) -> PoolInfo:
         out = PoolInfo()

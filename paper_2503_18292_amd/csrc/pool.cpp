@@ -83,58 +83,190 @@ int64_t first_clear(const std::vector<uint64_t>& v, int64_t begin, int64_t end) 
 
 bool kind_ok(const jenga_pool* p, int32_t kind) { return p && kind >= 0 && kind < int32_t(p->kinds.size()); }
 
-// Takes the lowest unused slot of an owned large page that is known to have one.
+// Lowest slot of an owned large page that is neither used nor evictable, or -1.
+int64_t first_empty(const Kind& k, int64_t large) {
+  const int64_t begin = large * k.per_large, end = (large + 1) * k.per_large;
+  int64_t i = begin;
+  while (i < end) {
+    const int64_t w = i >> 6;
+    uint64_t inv = ~(k.used[w] | k.cached[w]);
+    inv &= ~uint64_t(0) << (i & 63);
+    const int64_t word_end = (w + 1) << 6;
+    if (word_end > end) inv &= (uint64_t(1) << (end & 63)) - 1;
+    if (inv) return (w << 6) + __builtin_ctzll(inv);
+    i = word_end;
+  }
+  return -1;
+}
+
+void ensure_keys(jenga_pool* p, Kind& k) {
+  if (k.last_access.empty()) {
+    k.last_access.assign(size_t(p->n_large * k.per_large), 0);
+    k.prefix_length.assign(size_t(p->n_large * k.per_large), 0);
+  }
+}
+
+std::tuple<int64_t, int64_t, int32_t> small_key(const Kind& k, int32_t sid) {
+  if (k.last_access.empty()) return {0, 0, sid};
+  return {k.last_access[sid], -k.prefix_length[sid], sid};
+}
+
+void drop_from_room_sets(jenga_pool* p, Kind& k, int64_t large) {
+  k.with_room.erase(large);
+  auto it = k.with_room_by_request.find(p->large_request[large]);
+  if (it != k.with_room_by_request.end()) {
+    it->second.erase(large);
+    if (it->second.empty()) k.with_room_by_request.erase(it);
+  }
+}
+
+// Keeps the large page's membership and key in the evictable-large set in step with its
+// counters: member iff no small page is used and at least one is evictable (Sec. 5.4).
+void refresh_evictable_large(jenga_pool* p, int64_t large) {
+  auto& cur = p->evictable_large_key[large];
+  if (std::get<2>(cur) >= 0) {
+    p->evictable_large.erase(cur);
+    std::get<2>(cur) = -1;
+  }
+  const int32_t kind = p->large_kind[large];
+  if (kind < 0 || p->large_used[large] != 0 || p->large_cached[large] == 0) return;
+  const Kind& k = p->kinds[kind];
+  int64_t ts = std::numeric_limits<int64_t>::min(), len = std::numeric_limits<int64_t>::min();
+  for (int64_t s = large * k.per_large; s < (large + 1) * k.per_large; ++s) {
+    if (!bit_get(k.cached, s)) continue;
+    ts = std::max(ts, k.last_access.empty() ? 0 : k.last_access[s]);
+    len = std::max(len, k.prefix_length.empty() ? 0 : k.prefix_length[s]);
+  }
+  cur = {ts, -len, large};
+  p->evictable_large.insert(cur);
+}
+
+// A free large page becomes `kind`'s, all its small pages associated with `request`.
+void adopt_large(jenga_pool* p, int32_t kind, int64_t large, int64_t request) {
+  Kind& k = p->kinds[kind];
+  p->large_kind[large] = kind;
+  p->large_request[large] = request;
+  p->large_empty[large] = int32_t(k.per_large);
+  p->large_used[large] = 0;
+  p->large_cached[large] = 0;
+  ++k.owned_large;
+  k.with_room.insert(large);
+  k.with_room_by_request[request].insert(large);
+}
+
+// An owned large page whose small pages are all empty goes back to level 1.
+void return_large(jenga_pool* p, int64_t large) {
+  Kind& k = p->kinds[p->large_kind[large]];
+  drop_from_room_sets(p, k, large);
+  p->large_kind[large] = -1;
+  p->large_request[large] = 0;
+  p->large_empty[large] = p->large_used[large] = p->large_cached[large] = 0;
+  --k.owned_large;
+  p->free_large.insert(large);
+}
+
+// Takes the lowest empty slot of an owned large page that is known to have one.
 int32_t take_slot(jenga_pool* p, int32_t kind, int64_t large) {
   Kind& k = p->kinds[kind];
-  const int64_t sid = first_clear(k.used, large * k.per_large, (large + 1) * k.per_large);
+  const int64_t sid = first_empty(k, large);
   bit_set(k.used, sid);
   ++k.used_small;
-  if (--p->large_unused[large] == 0) {
-    k.with_room.erase(large);
-    auto it = k.with_room_by_request.find(p->large_request[large]);
-    if (it != k.with_room_by_request.end()) {
-      it->second.erase(large);
-      if (it->second.empty()) k.with_room_by_request.erase(it);
-    }
-  }
+  const bool was_evictable = p->large_used[large] == 0 && p->large_cached[large] > 0;
+  ++p->large_used[large];
+  if (--p->large_empty[large] == 0) drop_from_room_sets(p, k, large);
+  if (was_evictable) refresh_evictable_large(p, large);
   return int32_t(sid);
 }
 
-int alloc_small(jenga_pool* p, int32_t kind, int64_t request, int32_t* out) {
+struct Evicted {
+  int32_t* kinds;
+  int32_t* ids;
+  int32_t cap;
+  int32_t n;
+  void add(int32_t kind, int32_t sid) {
+    if (n < cap) {
+      if (kinds) kinds[n] = kind;
+      if (ids) ids[n] = sid;
+    }
+    ++n;
+  }
+};
+
+// allocate() of Sec. 4.1 in the order of Sec. 4.3, extended by the eviction steps of
+// Sec. 5.4.  With nothing evictable steps 3 and 5 find nothing and this is Sec. 4.3.
+int alloc_small(jenga_pool* p, int32_t kind, int64_t request, int32_t* out, Evicted* ev) {
   Kind& k = p->kinds[kind];
-  // step 1 (Sec. 4.3): an unused small page associated with this request
+  // step 1: an empty small page associated with this request
   auto mine = k.with_room_by_request.find(request);
   if (mine != k.with_room_by_request.end() && !mine->second.empty()) {
     *out = take_slot(p, kind, *mine->second.begin());
     return JENGA_OK;
   }
-  // step 2: a new large page; all its small pages become associated with the request
+  // step 2: an empty large page; all its small pages become associated with the request
   if (!p->free_large.empty()) {
     const int64_t large = *p->free_large.begin();
     p->free_large.erase(p->free_large.begin());
-    p->large_kind[large] = kind;
-    p->large_request[large] = request;
-    p->large_unused[large] = int32_t(k.per_large);
-    ++k.owned_large;
-    k.with_room.insert(large);
-    k.with_room_by_request[request].insert(large);
+    adopt_large(p, kind, large, request);
     *out = take_slot(p, kind, large);
     return JENGA_OK;
   }
-  // step 3: an unused small page of this kind associated with another request
+  // step 3: evict the least recently used evictable large page, of whatever kind
+  if (!p->evictable_large.empty()) {
+    const int64_t large = std::get<2>(*p->evictable_large.begin());
+    const int32_t old_kind = p->large_kind[large];
+    Kind& ko = p->kinds[old_kind];
+    for (int64_t s = large * ko.per_large; s < (large + 1) * ko.per_large; ++s) {
+      if (!bit_get(ko.cached, s)) continue;
+      ko.evictable.erase(small_key(ko, int32_t(s)));
+      bit_clear(ko.cached, s);
+      --ko.cached_small;
+      if (ev) ev->add(old_kind, int32_t(s));
+    }
+    p->large_cached[large] = 0;
+    refresh_evictable_large(p, large);          // leaves the set
+    drop_from_room_sets(p, ko, large);
+    --ko.owned_large;
+    p->large_kind[large] = -1;
+    adopt_large(p, kind, large, request);
+    *out = take_slot(p, kind, large);
+    return JENGA_OK;
+  }
+  // step 4: an empty small page of this kind associated with another request
   if (!k.with_room.empty()) {
     *out = take_slot(p, kind, *k.with_room.begin());
+    return JENGA_OK;
+  }
+  // step 5: evict the least recently used evictable small page of this kind
+  if (!k.evictable.empty()) {
+    const int32_t sid = std::get<2>(*k.evictable.begin());
+    k.evictable.erase(k.evictable.begin());
+    const int64_t large = sid / k.per_large;
+    const bool was_evictable = p->large_used[large] == 0;
+    bit_clear(k.cached, sid);
+    --k.cached_small;
+    --p->large_cached[large];
+    bit_set(k.used, sid);
+    ++k.used_small;
+    ++p->large_used[large];
+    if (was_evictable) refresh_evictable_large(p, large);
+    if (ev) ev->add(kind, sid);
+    *out = sid;
     return JENGA_OK;
   }
   return JENGA_ERR_OOM;
 }
 
-bool small_live(const jenga_pool* p, int32_t kind, int32_t sid) {
-  const Kind& k = p->kinds[kind];
-  return sid >= 0 && int64_t(sid) < p->n_large * k.per_large && bit_get(k.used, sid);
+bool small_in_range(const jenga_pool* p, int32_t kind, int32_t sid) {
+  return sid >= 0 && int64_t(sid) < p->n_large * p->kinds[kind].per_large;
 }
 
-int free_small(jenga_pool* p, int32_t kind, int32_t sid) {
+bool small_live(const jenga_pool* p, int32_t kind, int32_t sid) {
+  return small_in_range(p, kind, sid) && bit_get(p->kinds[kind].used, sid);
+}
+
+// free(small_page_id) of Sec. 4.1 (keep_cached false) or the end of a request under prefix
+// caching (keep_cached true: the page stays evictable, Sec. 5.4).
+int release_small(jenga_pool* p, int32_t kind, int32_t sid, bool keep_cached) {
   if (!small_live(p, kind, sid)) return JENGA_ERR_INVALID;
   Kind& k = p->kinds[kind];
   auto extra = k.extra_refs.find(sid);
@@ -145,26 +277,29 @@ int free_small(jenga_pool* p, int32_t kind, int32_t sid) {
   bit_clear(k.used, sid);
   --k.used_small;
   const int64_t large = sid / k.per_large;
-  const int64_t req = p->large_request[large];
-  if (++p->large_unused[large] == k.per_large) {
-    // every small page unused: back to the large-page allocator (Sec. 4.1 free())
-    k.with_room.erase(large);
-    auto it = k.with_room_by_request.find(req);
-    if (it != k.with_room_by_request.end()) {
-      it->second.erase(large);
-      if (it->second.empty()) k.with_room_by_request.erase(it);
-    }
-    p->large_kind[large] = -1;
-    p->large_request[large] = 0;
-    p->large_unused[large] = 0;
-    --k.owned_large;
-    p->free_large.insert(large);
+  --p->large_used[large];
+  if (keep_cached) {
+    bit_set(k.cached, sid);
+    ++k.cached_small;
+    ++p->large_cached[large];
+    k.evictable.insert(small_key(k, sid));
   } else {
-    k.with_room.insert(large);
-    k.with_room_by_request[req].insert(large);
+    if (p->large_empty[large]++ == 0) {
+      k.with_room.insert(large);
+      k.with_room_by_request[p->large_request[large]].insert(large);
+    }
+  }
+  if (p->large_used[large] == 0) {
+    if (p->large_cached[large] == 0) {
+      return_large(p, large);               // every small page empty (Sec. 4.1 free())
+    } else {
+      refresh_evictable_large(p, large);
+    }
   }
   return JENGA_OK;
 }
+
+int free_small(jenga_pool* p, int32_t kind, int32_t sid) { return release_small(p, kind, sid, false); }
 
 }  // namespace
 
@@ -208,10 +343,14 @@ int jenga_pool_create(void* device_base, int64_t pool_bytes, int64_t large_page_
       return JENGA_ERR_UNSUPPORTED;      // small ids are int32
     }
     k.used.assign(size_t((p->n_large * k.per_large + 63) / 64), 0);
+    k.cached.assign(k.used.size(), 0);
   }
   p->large_kind.assign(size_t(p->n_large), -1);
   p->large_request.assign(size_t(p->n_large), 0);
-  p->large_unused.assign(size_t(p->n_large), 0);
+  p->large_empty.assign(size_t(p->n_large), 0);
+  p->large_used.assign(size_t(p->n_large), 0);
+  p->large_cached.assign(size_t(p->n_large), 0);
+  p->evictable_large_key.assign(size_t(p->n_large), std::make_tuple(int64_t(0), int64_t(0), int64_t(-1)));
   for (int64_t i = 0; i < p->n_large; ++i) p->free_large.insert(p->free_large.end(), i);
   *out = p;
   return JENGA_OK;
@@ -225,7 +364,7 @@ int jenga_pool_destroy(jenga_pool* pool) {
 
 int jenga_alloc_small(jenga_pool* pool, int32_t kind, int64_t request, int32_t* out_small_id) {
   if (!kind_ok(pool, kind) || !out_small_id) return JENGA_ERR_INVALID;
-  return alloc_small(pool, kind, request, out_small_id);
+  return alloc_small(pool, kind, request, out_small_id, nullptr);
 }
 
 int jenga_ref_small(jenga_pool* pool, int32_t kind, int32_t small_id) {
@@ -257,7 +396,8 @@ int jenga_pool_kind_stats(const jenga_pool* pool, int32_t kind, jenga_kind_stats
   out->small_per_large = k.per_large;
   out->owned_large_pages = k.owned_large;
   out->used_small_pages = k.used_small;
-  out->unused_small_pages = k.owned_large * k.per_large - k.used_small;
+  out->unused_small_pages = k.owned_large * k.per_large - k.used_small - k.cached_small;
+  out->evictable_small_pages = k.cached_small;
   return JENGA_OK;
 }
 
@@ -310,7 +450,7 @@ int jenga_request_extend(jenga_pool* pool, int64_t request, int32_t kind, int64_
   std::vector<int32_t>& lst = rp.pages[kind];
   while (int64_t(lst.size()) < need) {
     int32_t sid = -1;
-    const int rc = alloc_small(pool, kind, request, &sid);
+    const int rc = alloc_small(pool, kind, request, &sid, nullptr);
     if (rc != JENGA_OK) return rc;
     lst.push_back(sid);
   }
@@ -403,6 +543,147 @@ int jenga_block_table_fill(const jenga_pool* pool, int32_t kind, const int64_t* 
     if (rc != JENGA_OK) return rc;
   }
   return JENGA_OK;
+}
+
+int jenga_alloc_small_evict(jenga_pool* pool, int32_t kind, int64_t request, int32_t* out_small_id,
+                            int32_t* evicted_kinds, int32_t* evicted_ids, int32_t capacity,
+                            int32_t* out_n_evicted) {
+  if (!kind_ok(pool, kind) || !out_small_id || capacity < 0) return JENGA_ERR_INVALID;
+  Evicted ev{evicted_kinds, evicted_ids, capacity, 0};
+  const int rc = alloc_small(pool, kind, request, out_small_id, &ev);
+  if (out_n_evicted) *out_n_evicted = ev.n;
+  return rc;
+}
+
+int jenga_release_small(jenga_pool* pool, int32_t kind, int32_t small_id, int32_t keep_cached) {
+  if (!kind_ok(pool, kind)) return JENGA_ERR_INVALID;
+  return release_small(pool, kind, small_id, keep_cached != 0);
+}
+
+int jenga_acquire_cached(jenga_pool* pool, int32_t kind, int32_t small_id) {
+  if (!kind_ok(pool, kind) || !small_in_range(pool, kind, small_id)) return JENGA_ERR_INVALID;
+  Kind& k = pool->kinds[kind];
+  if (!bit_get(k.cached, small_id)) return JENGA_ERR_INVALID;
+  k.evictable.erase(small_key(k, small_id));
+  bit_clear(k.cached, small_id);
+  --k.cached_small;
+  bit_set(k.used, small_id);
+  ++k.used_small;
+  const int64_t large = small_id / k.per_large;
+  --pool->large_cached[large];
+  const bool was_evictable = pool->large_used[large] == 0;
+  ++pool->large_used[large];
+  if (was_evictable) refresh_evictable_large(pool, large);
+  return JENGA_OK;
+}
+
+namespace {
+// Changes one LRU key of a used or evictable page and keeps the ordered sets in step.
+int set_key(jenga_pool* pool, int32_t kind, int32_t sid, bool is_time, int64_t value) {
+  if (!kind_ok(pool, kind) || !small_in_range(pool, kind, sid)) return JENGA_ERR_INVALID;
+  Kind& k = pool->kinds[kind];
+  const bool cached = bit_get(k.cached, sid);
+  if (!cached && !bit_get(k.used, sid)) return JENGA_ERR_INVALID;     // empty pages have no keys
+  ensure_keys(pool, k);
+  if (cached) k.evictable.erase(small_key(k, sid));
+  (is_time ? k.last_access : k.prefix_length)[sid] = value;
+  if (cached) {
+    k.evictable.insert(small_key(k, sid));
+    refresh_evictable_large(pool, sid / k.per_large);
+  }
+  return JENGA_OK;
+}
+}  // namespace
+
+int jenga_set_last_access(jenga_pool* pool, int32_t kind, int32_t small_id, int64_t time) {
+  return set_key(pool, kind, small_id, true, time);
+}
+
+int jenga_set_prefix_length(jenga_pool* pool, int32_t kind, int32_t small_id, int64_t length) {
+  return set_key(pool, kind, small_id, false, length);
+}
+
+int jenga_small_state(const jenga_pool* pool, int32_t kind, int32_t small_id, int32_t* out_state) {
+  if (!kind_ok(pool, kind) || !small_in_range(pool, kind, small_id) || !out_state) return JENGA_ERR_INVALID;
+  const Kind& k = pool->kinds[kind];
+  *out_state = bit_get(k.used, small_id) ? JENGA_PAGE_USED
+               : bit_get(k.cached, small_id) ? JENGA_PAGE_EVICTABLE : JENGA_PAGE_EMPTY;
+  return JENGA_OK;
+}
+
+int jenga_request_release(jenga_pool* pool, int64_t request, int32_t keep_cached) {
+  if (!pool) return JENGA_ERR_INVALID;
+  auto it = pool->requests.find(request);
+  if (it == pool->requests.end()) return JENGA_ERR_INVALID;
+  for (size_t kind = 0; kind < it->second.pages.size(); ++kind)
+    for (int32_t sid : it->second.pages[kind])
+      if (sid >= 0) release_small(pool, int32_t(kind), sid, keep_cached != 0);
+  pool->requests.erase(it);
+  return JENGA_OK;
+}
+
+int jenga_request_touch(jenga_pool* pool, int64_t request, int32_t kind, int64_t first_token,
+                        int64_t end_token, int64_t time) {
+  if (!kind_ok(pool, kind) || first_token < 0 || end_token < first_token) return JENGA_ERR_INVALID;
+  auto it = pool->requests.find(request);
+  if (it == pool->requests.end()) return JENGA_ERR_INVALID;
+  const std::vector<int32_t>& lst = it->second.pages[kind];
+  const int64_t T = pool->kinds[kind].desc.tokens_per_page;
+  const int64_t p_end = std::min<int64_t>(int64_t(lst.size()), (end_token + T - 1) / T);
+  for (int64_t pg = first_token / T; pg < p_end; ++pg)
+    if (lst[pg] >= 0) set_key(pool, kind, lst[pg], true, time);
+  return JENGA_OK;
+}
+
+int jenga_request_set_prefix_lengths(jenga_pool* pool, int64_t request, int32_t kind) {
+  if (!kind_ok(pool, kind)) return JENGA_ERR_INVALID;
+  auto it = pool->requests.find(request);
+  if (it == pool->requests.end()) return JENGA_ERR_INVALID;
+  const std::vector<int32_t>& lst = it->second.pages[kind];
+  const int64_t T = pool->kinds[kind].desc.tokens_per_page;
+  for (size_t pg = 0; pg < lst.size(); ++pg)
+    if (lst[pg] >= 0) set_key(pool, kind, lst[pg], false, int64_t(pg + 1) * T);
+  return JENGA_OK;
+}
+
+int jenga_possible_prefixes(int32_t rule, int32_t param, const uint8_t* is_hit, int32_t n_tokens,
+                            uint8_t* out_valid) {
+  if (n_tokens < 0 || (n_tokens > 0 && !is_hit) || !out_valid) return JENGA_ERR_INVALID;
+  if ((rule == JENGA_HIT_WINDOW || rule == JENGA_HIT_EVERY) && param < 1) return JENGA_ERR_INVALID;
+  out_valid[0] = 0;
+  switch (rule) {
+    case JENGA_HIT_FULL: {            // every token of the prefix cached
+      bool ok = true;
+      for (int32_t p = 1; p <= n_tokens; ++p) {
+        ok = ok && is_hit[p - 1];
+        out_valid[p] = ok;
+      }
+      return JENGA_OK;
+    }
+    case JENGA_HIT_WINDOW: {          // the last `param` tokens of the prefix cached
+      int32_t run = 0;                // cached tokens ending at p
+      for (int32_t p = 1; p <= n_tokens; ++p) {
+        run = is_hit[p - 1] ? run + 1 : 0;
+        out_valid[p] = run >= std::min(param, p);
+      }
+      return JENGA_OK;
+    }
+    case JENGA_HIT_EVERY:             // one cached state every `param` tokens
+      for (int32_t p = 1; p <= n_tokens; ++p) out_valid[p] = (p % param == 0) && is_hit[p - 1];
+      return JENGA_OK;
+    default:
+      return JENGA_ERR_INVALID;
+  }
+}
+
+int jenga_longest_common_prefix(const uint8_t* const* valid_sets, int32_t n_sets, int32_t n_tokens) {
+  if (!valid_sets || n_sets < 1 || n_tokens < 0) return JENGA_ERR_INVALID;
+  for (int32_t p = n_tokens; p >= 1; --p) {
+    bool all = true;
+    for (int32_t s = 0; s < n_sets && all; ++s) all = valid_sets[s] && valid_sets[s][p];
+    if (all) return p;
+  }
+  return 0;
 }
 
 const char* jenga_strerror(int status) {

@@ -4,6 +4,7 @@
 
 #include <cstdint>
 #include <set>
+#include <tuple>
 #include <unordered_map>
 #include <vector>
 
@@ -19,17 +20,24 @@ struct Kind {
   int32_t elem_bytes = 0;
   int32_t t_log2 = 0;
 
-  // level 2 state.  Bit `sid` of `used` is set while small page sid has references;
+  // level 2 state.  A small page is used (bit in `used`: it has references), evictable
+  // (bit in `cached`: valid contents, no references; Sec. 5.4) or empty (neither).
   // `extra_refs` holds (count - 1) for pages with more than one reference.
   std::vector<uint64_t> used;
+  std::vector<uint64_t> cached;
   std::unordered_map<int32_t, int32_t> extra_refs;
-  // large pages of this kind that still have an unused slot: all of them (step 3),
-  // and grouped by the request they are associated with (step 1).  Ordered, so the
-  // lowest-numbered one is *begin().
+  // LRU keys of Sec. 5.1, kept for used and evictable pages; allocated on first use
+  std::vector<int64_t> last_access;
+  std::vector<int64_t> prefix_length;
+  // large pages of this kind that still have an empty slot: all of them, and grouped by
+  // the request they are associated with.  Ordered: the lowest-numbered one is *begin().
   std::set<int64_t> with_room;
   std::unordered_map<int64_t, std::set<int64_t>> with_room_by_request;
+  // evictable small pages ordered by (last access, -prefix length, id): *begin() goes first
+  std::set<std::tuple<int64_t, int64_t, int32_t>> evictable;
   int64_t owned_large = 0;
   int64_t used_small = 0;
+  int64_t cached_small = 0;
 };
 
 struct RequestPages {
@@ -48,7 +56,13 @@ struct jenga_pool {
   // level 1 state
   std::vector<int32_t> large_kind;        // -1: free
   std::vector<int64_t> large_request;     // valid while large_kind >= 0
-  std::vector<int32_t> large_unused;      // unused slots left, valid while owned
+  std::vector<int32_t> large_empty;       // empty slots, valid while owned
+  std::vector<int32_t> large_used;        // used slots, valid while owned
+  std::vector<int32_t> large_cached;      // evictable slots, valid while owned
   std::set<int64_t> free_large;           // ordered: lowest-numbered first
+  // large pages with no used and at least one evictable small page, ordered by
+  // (latest last access of their evictable pages, -largest prefix length, page number)
+  std::set<std::tuple<int64_t, int64_t, int64_t>> evictable_large;
+  std::vector<std::tuple<int64_t, int64_t, int64_t>> evictable_large_key;   // key while in the set
   std::unordered_map<int64_t, jenga::RequestPages> requests;
 };
