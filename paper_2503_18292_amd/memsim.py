@@ -1,0 +1,129 @@
+"""Memory-utilisation simulation: the two-level allocator against homogeneous paging.
+
+Drives the library's host allocator (no GPU needed) with a synthetic serving trace --
+requests arrive, grow by decode steps, finish -- and records, over time, the bytes that are
+used (hold KV some layer still needs), wasted and unallocated, for
+  * this library: per-layer-type small pages in LCM large pages, window pages freed on
+    slide-out, request-aware placement (paper Sec. 4); waste = empty small pages inside owned
+    large pages plus the unfilled tail of each request's last page;
+  * homogeneous paging: one page size for all layers, every layer keeps every token
+    (paper Sec. 3.2); waste = KV of tokens a layer no longer (or never) needs.
+This is the experiment behind the paper's memory-timeline figure (Sec. 7.3) on synthetic
+traces; its datasets and models are not used.
+
+    python -m paper_2503_18292_amd.memsim --model ministral_like --trace dynamic
+"""
+from __future__ import annotations
+
+import argparse
+import json
+from dataclasses import dataclass
+from typing import List
+
+import numpy as np
+
+from . import api
+from .api import Pool, make_kind
+
+
+@dataclass
+class SimKind:
+    name: str
+    type: int                 # api.FULL / api.WINDOW
+    n_layers: int
+    window: int = 0
+
+
+MODELS = {
+    # shapes only (layer mix, window, KV heads, head size); no weights involved
+    "gemma2_like": dict(kinds=[SimKind("full", api.FULL, 21), SimKind("window", api.WINDOW, 21, 4096)],
+                        n_kv_heads=8, head_dim=256, max_len=8192),
+    "ministral_like": dict(kinds=[SimKind("full", api.FULL, 9), SimKind("window", api.WINDOW, 27, 32768)],
+                           n_kv_heads=8, head_dim=128, max_len=131072),
+}
+
+
+def make_trace(kind: str, n_requests: int, max_len: int, seed: int):
+    """(arrival step, prompt tokens, output tokens) per request."""
+    rng = np.random.default_rng(seed)
+    out = []
+    t = 0
+    for i in range(n_requests):
+        if kind == "static":          # everyone at the maximum context, all at once
+            out.append((0, max_len - 64, 64))
+        else:                         # staggered arrivals, log-uniform prompts, short outputs
+            prompt = int(np.exp(rng.uniform(np.log(max_len / 32), np.log(max_len * 0.9))))
+            out.append((t, prompt, int(rng.integers(32, 128))))
+            t += int(rng.integers(0, 40))
+    return out
+
+
+def simulate(model: str, trace_kind: str, n_requests: int = 24, pool_gib: float = 64.0,
+             tokens_per_page: int = 16, seed: int = 0, sample_every: int = 16):
+    m = MODELS[model]
+    kinds = [make_kind(k.type, api.BF16, k.n_layers, m["n_kv_heads"], m["head_dim"], tokens_per_page, k.window)
+             for k in m["kinds"]]
+    per_tok_layer = 2 * m["n_kv_heads"] * m["head_dim"] * 2
+    large = api.lcm_page_bytes(kinds)
+    pool = Pool(None, int(pool_gib * 2**30), kinds, large)
+    n_layers = sum(k.n_layers for k in m["kinds"])
+    trace = make_trace(trace_kind, n_requests, m["max_len"], seed)
+    horizon = max(a + o for a, _, o in trace) + 1
+    length = {}                                   # live request -> cached tokens
+    rows = []
+    for step in range(horizon):
+        for rid, (arr, prompt, out_len) in enumerate(trace):
+            if arr == step:
+                length[rid] = prompt              # prefill
+            elif rid in length:
+                length[rid] += 1                  # one decode step
+            if rid in length:
+                for k in range(len(kinds)):
+                    pool.request_extend(rid, k, length[rid])
+                if step == arr + out_len:
+                    pool.request_free(rid)
+                    del length[rid]
+        if step % sample_every and step != horizon - 1:
+            continue
+        info = pool.get_info()
+        needed = 0                                # bytes some layer still needs
+        for L in length.values():
+            for k in m["kinds"]:
+                needed += (min(L, k.window) if k.window else L) * k.n_layers * per_tok_layer
+        owned = (info.n_large_pages - info.free_large_pages) * large
+        ours_waste = owned - needed
+        homo_alloc = sum(-(-L // tokens_per_page) * tokens_per_page for L in length.values()) * n_layers * per_tok_layer
+        rows.append(dict(step=step, live=len(length), needed=needed, ours_allocated=owned,
+                         ours_wasted=ours_waste, homogeneous_allocated=homo_alloc,
+                         homogeneous_wasted=homo_alloc - needed))
+    pool.destroy()
+    tot_need = sum(r["needed"] for r in rows)
+    summary = dict(
+        model=model, trace=trace_kind, requests=n_requests, large_page_bytes=large,
+        ours_waste_fraction=sum(r["ours_wasted"] for r in rows) / max(1, sum(r["ours_allocated"] for r in rows)),
+        homogeneous_waste_fraction=sum(r["homogeneous_wasted"] for r in rows)
+        / max(1, sum(r["homogeneous_allocated"] for r in rows)),
+        peak_ours_bytes=max(r["ours_allocated"] for r in rows),
+        peak_homogeneous_bytes=max(r["homogeneous_allocated"] for r in rows),
+        mean_needed_bytes=tot_need / len(rows))
+    return summary, rows
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--model", default="ministral_like", choices=sorted(MODELS))
+    ap.add_argument("--trace", default="dynamic", choices=["static", "dynamic"])
+    ap.add_argument("--requests", type=int, default=24)
+    ap.add_argument("--pool-gib", type=float, default=64.0)
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--timeline", action="store_true", help="also print one JSON line per sample")
+    a = ap.parse_args()
+    summary, rows = simulate(a.model, a.trace, a.requests, a.pool_gib, seed=a.seed)
+    if a.timeline:
+        for r in rows:
+            print(json.dumps(r))
+    print(json.dumps(summary))
+
+
+if __name__ == "__main__":
+    main()
