@@ -44,6 +44,10 @@ def parse():
                     help="do not bracket the decode kernel with events (roofline.achieved becomes null)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle timing")
+    ap.add_argument("--mode", default="decode", choices=["decode", "kv_write", "allocator"],
+                    help="decode: the benchmark proper; kv_write: bulk K/V write of a prefill chunk; "
+                         "allocator: host microseconds per allocator call, library against oracle")
+    ap.add_argument("--chunk", type=int, default=512, help="kv_write: tokens written per request and call")
     ap.add_argument("--copy-calibration", type=float, default=0.0, metavar="GiB",
                     help="instead of the benchmark, run the library's plain copy and read kernels over "
                          "a buffer of this size (to calibrate profiler byte counters) and exit")
@@ -129,6 +133,89 @@ def copy_calibration(gib: float):
     print(json.dumps({"copy_calibration": out}), flush=True)
 
 
+def kv_write_bench(args):
+    """Bulk K/V write (jenga_kv_write_range): every request writes its last `chunk` cached tokens."""
+    import numpy as np
+    import torch
+    from paper_2503_18292_amd.runner import DecodeRunner
+    from workloads import configs, values
+    cfg = configs.ALL[args.workload]()
+    r = DecodeRunner(cfg, args.seed)
+    r.build_contexts()
+    r.host_step()
+    dev = r.device
+    out = {}
+    for k in r.attn_kinds:
+        kd = cfg.kinds[k]
+        if kd.type == configs.CROSS:
+            continue
+        B = cfg.batch
+        n = np.minimum(args.chunk, r.ctx).astype(np.int32)
+        cu = np.zeros(B + 1, dtype=np.int32)
+        cu[1:] = np.cumsum(n)
+        total = int(cu[-1])
+        # several distinct sources in rotation, so a call never finds its input in the 256 MB
+        # memory-side cache left there by the previous call
+        one = values.normal((2, total, kd.n_kv_heads, kd.head_dim), kd.dtype, cfg.value_sigma, args.seed, 9).to(dev)
+        srcs = [one] + [one.clone() for _ in range(5)]
+        cu_d = torch.from_numpy(cu).to(dev)
+        start = torch.from_numpy((r.ctx - n).astype(np.int32)).to(dev)
+        layers = list(range(kd.n_layers))
+        for layer in layers[:2]:
+            r.pool.kv_write_range(k, layer, one[0], one[1], cu_d, start, r.tables[k])
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            for layer in layers:
+                src = srcs[layer % len(srcs)]
+                r.pool.kv_write_range(k, layer, src[0], src[1], cu_d, start, r.tables[k])
+        e1.record()
+        torch.cuda.synchronize()
+        nbytes = total * kd.bytes_per_token_per_layer
+        us = e0.elapsed_time(e1) * 1e3 / (args.steps * len(layers))
+        # every byte is read once from the source and written once into the pool
+        out[kd.name] = {"tokens_per_call": total, "bytes_written_per_call": nbytes, "us_per_call": round(us, 2),
+                        "write_GBps": round(nbytes / us / 1e3, 1), "read_plus_write_GBps": round(2 * nbytes / us / 1e3, 1)}
+    print(json.dumps({"mode": "kv_write", "workload": cfg.name, "chunk": args.chunk, "kinds": out,
+                      "roofline": {"bound": "hbm", "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                   "achieved": max(v["read_plus_write_GBps"] for v in out.values()),
+                                   "frac": round(max(v["read_plus_write_GBps"] for v in out.values()) / HBM_PEAK_GBS, 4)}}),
+          flush=True)
+    r.close()
+
+
+def allocator_bench(args):
+    """Host cost of the allocator: the workload's build + step + finish scripts, library and oracle."""
+    from oracle.alloc import OraclePool, OracleRequests, lcm_bytes
+    from paper_2503_18292_amd import api
+    from paper_2503_18292_amd.runner import kind_descs
+    from workloads import configs, scripts
+    cfg = configs.ALL[args.workload]()
+    ctx = scripts.sample_ctx(cfg, args.seed)
+    ops = (scripts.build_script(cfg, ctx, args.seed) + scripts.step_script(cfg, ctx)
+           + scripts.finish_script(cfg, args.seed))
+    descs = kind_descs(cfg)
+    large = api.lcm_page_bytes(descs)
+    n_large = cfg.pool_large_pages or scripts.pool_large_pages_needed(cfg, ctx, large)
+    lib = api.Pool(None, n_large * large, descs)
+    t0 = time.perf_counter()
+    scripts.run_script(ops, lib)
+    t_lib = time.perf_counter() - t0
+    pages = sum(-(-int(c + 1) // k.tokens_per_page) for c in ctx for k in cfg.kinds if k.type in ("full", "window"))
+    S = [k.small_page_bytes for k in cfg.kinds]
+    ora_pool = OraclePool(n_large * lcm_bytes(S), S)
+    ora = OracleRequests(ora_pool, [k.tokens_per_page for k in cfg.kinds], [k.window for k in cfg.kinds])
+    t0 = time.perf_counter()
+    scripts.run_script(ops, ora)
+    t_ora = time.perf_counter() - t0
+    print(json.dumps({"mode": "allocator", "workload": cfg.name, "script_ops": len(ops),
+                      "small_pages_allocated_at_least": pages,
+                      "library_seconds": round(t_lib, 4), "library_us_per_page": round(t_lib / pages * 1e6, 3),
+                      "oracle_seconds": round(t_ora, 3), "oracle_us_per_page": round(t_ora / pages * 1e6, 2),
+                      "note": "library time includes the ctypes call per request-level op"}), flush=True)
+
+
 def main():
     args = parse()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -145,6 +232,10 @@ def main():
     _lib.load()     # no library, no benchmark: there is no other path
     if args.copy_calibration > 0:
         return copy_calibration(args.copy_calibration)
+    if args.mode == "allocator":
+        return allocator_bench(args)
+    if args.mode == "kv_write":
+        return kv_write_bench(args)
     cfg = configs.ALL[args.workload]()
     total_steps = 2 * args.steps + args.warmup
     t_setup = time.perf_counter()

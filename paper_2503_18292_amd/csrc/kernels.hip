@@ -756,24 +756,18 @@ __global__ __launch_bounds__(256) void kv_append_kernel(
   *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
 }
 
-// Bulk write of a run of tokens per request (chunked prefill): one thread per 16 bytes.
-// Source rows are token-major, [token][kv head][D]; request b owns rows
-// [cu_tokens[b], cu_tokens[b+1]) and its first row is sequence position start_pos[b].
+// Bulk write of a run of tokens per request (chunked prefill).  One block per source token
+// row: the request and page lookups are wave-uniform (scalar loads), the threads then copy the
+// row's 2 * n_kv_heads * D * e bytes 16 at a time.  Source rows are token-major,
+// [token][kv head][D]; request b owns rows [cu_tokens[b], cu_tokens[b+1]) and its first row is
+// sequence position start_pos[b].
 __global__ __launch_bounds__(256) void kv_write_range_kernel(
     char* __restrict__ layer_base, int64_t small_bytes, int32_t head_stride, int32_t v_offset,
     int32_t t_log2, int32_t n_kv_heads, int32_t row_bytes, const char* __restrict__ k_src,
     const char* __restrict__ v_src, const int32_t* __restrict__ cu_tokens,
     const int32_t* __restrict__ start_pos, const int32_t* __restrict__ block_table,
-    int32_t bt_stride, int32_t batch, int64_t total_chunks) {
-  const int chunks = row_bytes / 16;
-  const int64_t idx = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
-  if (idx >= total_chunks) return;
-  const int c = int(idx % chunks);
-  int64_t r = idx / chunks;
-  const int is_v = int(r & 1);
-  r >>= 1;
-  const int h = int(r % n_kv_heads);
-  const int tok = int(r / n_kv_heads);
+    int32_t bt_stride, int32_t batch) {
+  const int tok = blockIdx.x;
   // request of this token: last b with cu_tokens[b] <= tok
   int lo = 0, hi = batch;
   while (hi - lo > 1) {
@@ -787,10 +781,19 @@ __global__ __launch_bounds__(256) void kv_write_range_kernel(
   if (pos < 0 || page >= bt_stride) return;
   const int sid = block_table[int64_t(b) * bt_stride + page];
   if (sid < 0) return;                            // page not resident (e.g. already slid out)
-  const char* src = (is_v ? v_src : k_src) + (int64_t(tok) * n_kv_heads + h) * row_bytes + c * 16;
-  char* dst = layer_base + int64_t(sid) * small_bytes + int64_t(h) * head_stride +
-              (is_v ? v_offset : 0) + (pos & ((1 << t_log2) - 1)) * row_bytes + c * 16;
-  *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
+  const int chunks = row_bytes / 16;              // 16-byte pieces per (head, K or V) row
+  char* page_base = layer_base + int64_t(sid) * small_bytes + (pos & ((1 << t_log2) - 1)) * row_bytes;
+  const char* k_row = k_src + int64_t(tok) * n_kv_heads * row_bytes;
+  const char* v_row = v_src + int64_t(tok) * n_kv_heads * row_bytes;
+  for (int i = threadIdx.x; i < 2 * n_kv_heads * chunks; i += blockDim.x) {
+    const int is_v = i >= n_kv_heads * chunks;
+    const int j = is_v ? i - n_kv_heads * chunks : i;     // 16-byte piece inside the token's K (or V) rows
+    const int h = j / chunks;
+    const int c = j - h * chunks;
+    const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>((is_v ? v_row : k_row) + j * 16));
+    __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(page_base + int64_t(h) * head_stride +
+                                                           (is_v ? v_offset : 0) + c * 16));
+  }
 }
 
 __global__ __launch_bounds__(256) void stream_copy_kernel(u32x4* __restrict__ dst,
@@ -988,15 +991,14 @@ int jenga_kv_write_range(const jenga_pool* pool, int32_t kind, int32_t layer, co
   if (!aligned16(k_src) || !aligned16(v_src)) return JENGA_ERR_ALIGN;
   if (batch == 0 || total_tokens == 0) return JENGA_OK;
   const int row_bytes = k.desc.head_dim * k.elem_bytes;
-  const int64_t total_chunks = int64_t(total_tokens) * k.desc.n_kv_heads * 2 * (row_bytes / 16);
-  const int64_t blocks = (total_chunks + 255) / 256;
-  if (blocks > 0x7fffffff) return JENGA_ERR_UNSUPPORTED;
-  hipLaunchKernelGGL(kv_write_range_kernel, dim3(unsigned(blocks)), dim3(256), 0,
+  const int per_token = k.desc.n_kv_heads * 2 * (row_bytes / 16);
+  const int threads = per_token >= 256 ? 256 : per_token >= 128 ? 128 : 64;
+  hipLaunchKernelGGL(kv_write_range_kernel, dim3(unsigned(total_tokens)), dim3(threads), 0,
                      static_cast<hipStream_t>(stream), pool->base + int64_t(layer) * k.slice_bytes,
                      k.small_bytes, int32_t(2 * k.desc.tokens_per_page * row_bytes),
                      int32_t(k.desc.tokens_per_page * row_bytes), k.t_log2, k.desc.n_kv_heads,
                      row_bytes, static_cast<const char*>(k_src), static_cast<const char*>(v_src),
-                     cu_tokens, start_pos, block_table, bt_stride, batch, total_chunks);
+                     cu_tokens, start_pos, block_table, bt_stride, batch);
   return hip_status();
 }
 
