@@ -275,6 +275,11 @@ int64_t jenga_decode_workspace_bytes(const jenga_pool* pool, int32_t kind, int32
  * (for CROSS kinds L_b is the encoder length).  fp32 accumulation; out is fp32
  * [batch][n_q_heads][head_dim]; L_b <= 0 gives zeros.
  *   q            device, [batch][n_q_heads][head_dim] in the kind's dtype, 16-byte aligned
+ *   k_new, v_new both NULL, or the new token's rows exactly as for jenga_kv_append (FULL and
+ *                WINDOW kinds only): the append is then done inside the decode kernel -- the
+ *                wavefront that reads a request's last page takes the row at position L - 1
+ *                from k_new / v_new, stores it into the page, and attends to it -- which saves
+ *                the separate jenga_kv_append launch.  Results are identical.
  *   block_table  device int32 [batch][bt_stride]; every page overlapping Vis_b must be
  *                resident (>= 0); other entries are never read
  *   seq_lens     device int32 [batch], each <= max_seq_len (larger ones are clamped)
@@ -287,6 +292,7 @@ int64_t jenga_decode_workspace_bytes(const jenga_pool* pool, int32_t kind, int32
  * Errors: INVALID, ALIGN, WORKSPACE, UNSUPPORTED (G not in {1,2,4,8}, batch > 1024), HIP. */
 int jenga_paged_decode(const jenga_pool* pool, int32_t kind, int32_t layer,
                        const void* q, int32_t n_q_heads,
+                       const void* k_new, const void* v_new,
                        const int32_t* block_table, int32_t bt_stride,
                        const int32_t* seq_lens, int32_t batch, int32_t max_seq_len,
                        int32_t window, float scale, int32_t pages_per_split,
@@ -297,6 +303,7 @@ int jenga_paged_decode(const jenga_pool* pool, int32_t kind, int32_t layer,
  * log-sum-exp rule  m* = max m_i,  out = sum_i acc_i 2^(m_i - m*) / sum_i l_i 2^(m_i - m*). */
 int jenga_paged_decode_partial(const jenga_pool* pool, int32_t kind, int32_t layer,
                                const void* q, int32_t n_q_heads,
+                               const void* k_new, const void* v_new,
                                const int32_t* block_table, int32_t bt_stride,
                                const int32_t* seq_lens, int32_t batch, int32_t max_seq_len,
                                int32_t window, float scale, int32_t pages_per_split,

@@ -67,9 +67,9 @@ SIGNATURES = {
     "jenga_kv_write_range": (C.c_int, [c_vp, c_i32, c_i32, c_vp, c_vp, c_vp, c_vp, c_vp, c_i32, c_i32, c_i32, c_vp]),
     "jenga_decode_num_partitions": (C.c_int, [c_vp, c_i32, c_i32, c_i32, c_i32, c_i32, c_i32]),
     "jenga_decode_workspace_bytes": (c_i64, [c_vp, c_i32, c_i32, c_i32, c_i32, c_i32, c_i32]),
-    "jenga_paged_decode": (C.c_int, [c_vp, c_i32, c_i32, c_vp, c_i32, c_vp, c_i32, c_vp, c_i32,
+    "jenga_paged_decode": (C.c_int, [c_vp, c_i32, c_i32, c_vp, c_i32, c_vp, c_vp, c_vp, c_i32, c_vp, c_i32,
                                      c_i32, c_i32, c_f32, c_i32, c_vp, c_i64, c_vp, c_vp]),
-    "jenga_paged_decode_partial": (C.c_int, [c_vp, c_i32, c_i32, c_vp, c_i32, c_vp, c_i32, c_vp,
+    "jenga_paged_decode_partial": (C.c_int, [c_vp, c_i32, c_i32, c_vp, c_i32, c_vp, c_vp, c_vp, c_i32, c_vp,
                                              c_i32, c_i32, c_i32, c_f32, c_i32, c_vp, c_i64, c_vp]),
     "jenga_splitk_reduce": (C.c_int, [c_vp, c_i32, c_i32, c_vp, c_i32, c_i32, c_i32, c_i32, c_vp,
                                       c_i64, c_vp, c_vp]),

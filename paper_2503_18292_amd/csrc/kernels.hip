@@ -56,6 +56,7 @@ struct DecodeParams {
   int32_t t_log2;
   int32_t n_kv_heads;
   int32_t n_q_heads;
+  int32_t max_page_id;        // ids read from the block table are clamped to [0, max_page_id]
   const void* q;
   const int32_t* block_table;
   int32_t bt_stride;
@@ -66,6 +67,8 @@ struct DecodeParams {
   float scale_log2;           // softmax scale * log2(e): scores live in the base-2 domain
   int32_t chunk_tiles;        // > 0: tiles per partition; 0: ceil(W / gridDim.x)
   int32_t min_chunk_tiles;    // lower bound of the automatic chunk
+  const void* k_new;          // fused append: [batch][n_kv_heads][D] rows of the token at L - 1, or NULL
+  const void* v_new;
   float* ws_acc;              // [slot][G][D]
   float* ws_ml;               // [slot][G][2]  (running max, running sum)
 };
@@ -232,16 +235,24 @@ struct PageIds {
   const int32_t* row;   // block-table entry of relative page 0
   int n_pages;
   int lane;
+  int max_id;
   int reg[2];
 
+  // A table entry that is negative or past the pool (a caller error: pages of the visible
+  // range must be resident) is clamped, so the kernel reads wrong data rather than faulting.
   __device__ __forceinline__ int fetch(int first) const {
     const int i = first + lane;
-    return i < n_pages ? row[i] : 0;
+    return i < n_pages ? min(max(row[i], 0), max_id) : 0;
   }
-  __device__ __forceinline__ void init(const int32_t* r, int n, int l) {
-    row = r; n_pages = n; lane = l;
+  __device__ __forceinline__ void init(const int32_t* r, int n, int l, int max_page_id) {
+    row = r; n_pages = n; lane = l; max_id = max_page_id;
     reg[0] = fetch(0);
     reg[1] = fetch(kWave);
+  }
+  // true when the table entry itself is a page of the pool (used before writing into it)
+  __device__ __forceinline__ bool writable(int page_rel) const {
+    const int raw = row[page_rel];
+    return raw >= 0 && raw <= max_id;
   }
   __device__ __forceinline__ int get(int page_rel) const {
     const int r = (page_rel & kWave) ? reg[1] : reg[0];
@@ -306,7 +317,8 @@ struct QuadEngine {
   static_assert(KCH >= 2 && KCH <= 8, "row size");
 
   __device__ static void run(const DecodeParams& p, int lane, int b, int kvh, int L, int tile0,
-                             int n_tiles, int64_t slot, float* lds) {
+                             int n_tiles, int append_tile, int64_t slot, float* lds) {
+    const bool append = append_tile >= 0;
     int lo_tok, p_lo, p_hi;
     visible_pages(L, p.window, 4, &lo_tok, &p_lo, &p_hi);
     const int page0 = p_lo + tile0 * PPT;
@@ -315,7 +327,7 @@ struct QuadEngine {
     float (*s_prob)[PPT * T][G] = reinterpret_cast<float (*)[PPT * T][G]>(lds);
 
     PageIds ids;
-    ids.init(p.block_table + int64_t(b) * p.bt_stride + page0, n_pages, lane);
+    ids.init(p.block_table + int64_t(b) * p.bt_stride + page0, n_pages, lane, p.max_page_id);
 
     const char* kv_base = p.layer_base + int64_t(kvh) * p.head_stride;   // wave-uniform
     const unsigned k_voff = (lane >> 2) * ROW + (lane & 3) * 16;         // K geometry
@@ -340,6 +352,19 @@ struct QuadEngine {
       l[g] = 0.f;
 #pragma unroll
       for (int j = 0; j < EPL; ++j) acc[g][j] = 0.f;
+    }
+
+    // Fused append: the wavefront whose chunk holds the tile of the newest token (position
+    // L - 1) takes that token's rows from k_new / v_new instead of the pool, and stores them
+    // into the page.
+    u32x4 k_app[KCH], v_app;
+    if (append) {
+      const char* kn = static_cast<const char*>(p.k_new) + (int64_t(b) * p.n_kv_heads + kvh) * ROW;
+      const char* vn = static_cast<const char*>(p.v_new) + (int64_t(b) * p.n_kv_heads + kvh) * ROW;
+#pragma unroll
+      for (int c = 0; c < KCH; ++c)
+        k_app[c] = *reinterpret_cast<const u32x4*>(kn + c * 64 + (lane & 3) * 16);
+      v_app = *reinterpret_cast<const u32x4*>(vn + (lane % LPT) * 16);
     }
 
     auto load_pages = [&](int tile, unsigned voff, int step, u32x4* buf) {
@@ -372,6 +397,33 @@ struct QuadEngine {
 
     auto step = [&](int tile, u32x4* kbuf, u32x4* vbuf, u32x4* v_next) {
       if (tile + 1 < n_tiles) load_pages(tile + 1, v_voff, 1024, v_next);
+
+      if (tile == append_tile) {
+        const int pos = L - 1;
+        const int page_rel = (pos >> 4) - page0;
+        const int pp_new = page_rel - tile * PPT;           // page of the tile that holds the new token
+        const int t_new = pp_new * T + (pos & 15);          // its index inside the tile
+        char* pb = const_cast<char*>(kv_base) + int64_t(ids.get(page_rel)) * p.small_bytes;
+        const bool store = ids.writable(page_rel);
+        if (k_tok == (pos & 15)) {
+#pragma unroll
+          for (int c = 0; c < KCH; ++c) {
+            if (store) *reinterpret_cast<u32x4*>(pb + k_voff + c * 64) = k_app[c];
+#pragma unroll
+            for (int pp = 0; pp < PPT; ++pp)
+              if (pp == pp_new) kbuf[pp * KCH + c] = k_app[c];
+          }
+        }
+        bool mine = false;
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+          if ((i / KCH) * T + (i % KCH) * TPL + v_grp == t_new) {
+            vbuf[i] = v_app;
+            mine = true;
+          }
+        }
+        if (mine && store) *reinterpret_cast<u32x4*>(pb + V_OFF + (pos & 15) * ROW + (lane % LPT) * 16) = v_app;
+      }
 
       // one score per (page of the tile, query head) and lane: token k_tok of that page
       float s[PPT][G];
@@ -493,7 +545,8 @@ struct RowEngine {
   static constexpr int kLdsFloats = 0;
 
   __device__ static void run(const DecodeParams& p, int lane, int b, int kvh, int L, int tile0,
-                             int n_tiles, int64_t slot, float*) {
+                             int n_tiles, int append_tile, int64_t slot, float*) {
+    const bool append = append_tile >= 0;
     int lo_tok, p_lo, p_hi;
     visible_pages(L, p.window, p.t_log2, &lo_tok, &p_lo, &p_hi);
     const int t_mask = (1 << p.t_log2) - 1;
@@ -505,7 +558,7 @@ struct RowEngine {
     const int abs0 = (page0 << p.t_log2) + tok_off0;        // absolute index of the chunk's first token
 
     PageIds ids;
-    ids.init(p.block_table + int64_t(b) * p.bt_stride + page0, n_pages, lane);
+    ids.init(p.block_table + int64_t(b) * p.bt_stride + page0, n_pages, lane, p.max_page_id);
 
     const int sub = lane % LPT;
     const int grp = lane / LPT;
@@ -543,11 +596,39 @@ struct RowEngine {
       }
     };
 
+    // fused append (see the quad engine): rows of the token at L - 1 come from k_new / v_new
+    u32x4 k_app = u32x4{0, 0, 0, 0}, v_app = u32x4{0, 0, 0, 0};
+    if (append) {
+      const int64_t off = (int64_t(b) * p.n_kv_heads + kvh) * ROW + sub * 16;
+      k_app = *reinterpret_cast<const u32x4*>(static_cast<const char*>(p.k_new) + off);
+      v_app = *reinterpret_cast<const u32x4*>(static_cast<const char*>(p.v_new) + off);
+    }
+
     u32x4 kbuf[NL], vbuf[NL];
     load_tile(0, 0, kbuf);
 
     for (int tile = 0; tile < n_tiles; ++tile) {
       load_tile(tile, p.v_offset, vbuf);
+
+      if (tile == append_tile) {
+        const int pos = L - 1;
+        const int page_rel = (pos >> p.t_log2) - page0;
+        bool mine = false;
+#pragma unroll
+        for (int i = 0; i < NL; ++i) {
+          if (abs0 + tile * TT + i * TPL + grp == pos) {
+            kbuf[i] = k_app;
+            vbuf[i] = v_app;
+            mine = true;
+          }
+        }
+        char* dst = const_cast<char*>(head_base) + int64_t(ids.get(page_rel)) * p.small_bytes +
+                    (pos & t_mask) * ROW - grp * ROW;     // head_base carries lane * 16 = grp * ROW + sub * 16
+        if (mine && ids.writable(page_rel)) {
+          *reinterpret_cast<u32x4*>(dst) = k_app;
+          *reinterpret_cast<u32x4*>(dst + p.v_offset) = v_app;
+        }
+      }
 
       float s[NL][G];
 #pragma unroll
@@ -659,7 +740,16 @@ __global__ __launch_bounds__(kWave) void decode_partial_kernel(const DecodeParam
     const int tile0 = rem - kvh * tiles_b;
     const int xe = min(x1, start_b + (kvh + 1) * tiles_b);
     const int64_t slot = int64_t(b) * p.n_kv_heads + kvh + blockIdx.x;
-    Eng::run(p, lane, b, kvh, s_len[b], tile0, xe - x, slot, s_eng);
+    // fused append: the chunk that holds the tile of the newest token (position L - 1) writes it
+    int append_tile = -1;
+    if (p.k_new != nullptr) {
+      const int L = s_len[b];
+      int lo_tok, p_lo, p_hi;
+      visible_pages(L, p.window, p.t_log2, &lo_tok, &p_lo, &p_hi);
+      const int t_pos = ((L - 1) - (p_lo << p.t_log2)) >> Eng::kTileLog2;
+      if (t_pos >= tile0 && t_pos < tile0 + (xe - x)) append_tile = t_pos - tile0;
+    }
+    Eng::run(p, lane, b, kvh, s_len[b], tile0, xe - x, append_tile, slot, s_eng);
     x = xe;
   }
 }
@@ -732,7 +822,7 @@ __global__ __launch_bounds__(256) void kv_append_kernel(
     char* __restrict__ layer_base, int64_t small_bytes, int32_t head_stride, int32_t v_offset,
     int32_t t_log2, int32_t n_kv_heads, int32_t row_bytes, const char* __restrict__ k_new,
     const char* __restrict__ v_new, const int32_t* __restrict__ block_table, int32_t bt_stride,
-    const int32_t* __restrict__ seq_lens, int32_t batch) {
+    const int32_t* __restrict__ seq_lens, int32_t batch, int32_t max_page_id) {
   const int chunks = row_bytes / 16;                       // 16-byte chunks per row
   const int64_t per_req = int64_t(n_kv_heads) * 2 * chunks;
   const int64_t idx = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
@@ -749,7 +839,7 @@ __global__ __launch_bounds__(256) void kv_append_kernel(
   const int page = pos >> t_log2;
   if (page >= bt_stride) return;
   const int sid = block_table[int64_t(b) * bt_stride + page];
-  if (sid < 0) return;
+  if (sid < 0 || sid > max_page_id) return;
   const char* src = (is_v ? v_new : k_new) + (int64_t(b) * n_kv_heads + h) * row_bytes + c * 16;
   char* dst = layer_base + int64_t(sid) * small_bytes + int64_t(h) * head_stride +
               (is_v ? v_offset : 0) + (pos & ((1 << t_log2) - 1)) * row_bytes + c * 16;
@@ -766,7 +856,7 @@ __global__ __launch_bounds__(256) void kv_write_range_kernel(
     int32_t t_log2, int32_t n_kv_heads, int32_t row_bytes, const char* __restrict__ k_src,
     const char* __restrict__ v_src, const int32_t* __restrict__ cu_tokens,
     const int32_t* __restrict__ start_pos, const int32_t* __restrict__ block_table,
-    int32_t bt_stride, int32_t batch) {
+    int32_t bt_stride, int32_t batch, int32_t max_page_id) {
   const int tok = blockIdx.x;
   // request of this token: last b with cu_tokens[b] <= tok
   int lo = 0, hi = batch;
@@ -780,7 +870,7 @@ __global__ __launch_bounds__(256) void kv_write_range_kernel(
   const int page = pos >> t_log2;
   if (pos < 0 || page >= bt_stride) return;
   const int sid = block_table[int64_t(b) * bt_stride + page];
-  if (sid < 0) return;                            // page not resident (e.g. already slid out)
+  if (sid < 0 || sid > max_page_id) return;       // page not resident (e.g. already slid out)
   const int chunks = row_bytes / 16;              // 16-byte pieces per (head, K or V) row
   char* page_base = layer_base + int64_t(sid) * small_bytes + (pos & ((1 << t_log2) - 1)) * row_bytes;
   const char* k_row = k_src + int64_t(tok) * n_kv_heads * row_bytes;
@@ -974,7 +1064,7 @@ int jenga_kv_append(const jenga_pool* pool, int32_t kind, int32_t layer, const v
                      k.small_bytes, int32_t(2 * k.desc.tokens_per_page * row_bytes),
                      int32_t(k.desc.tokens_per_page * row_bytes), k.t_log2, k.desc.n_kv_heads,
                      row_bytes, static_cast<const char*>(k_new), static_cast<const char*>(v_new),
-                     block_table, bt_stride, seq_lens, batch);
+                     block_table, bt_stride, seq_lens, batch, int32_t(pool->n_large * k.per_large - 1));
   return hip_status();
 }
 
@@ -998,7 +1088,8 @@ int jenga_kv_write_range(const jenga_pool* pool, int32_t kind, int32_t layer, co
                      k.small_bytes, int32_t(2 * k.desc.tokens_per_page * row_bytes),
                      int32_t(k.desc.tokens_per_page * row_bytes), k.t_log2, k.desc.n_kv_heads,
                      row_bytes, static_cast<const char*>(k_src), static_cast<const char*>(v_src),
-                     cu_tokens, start_pos, block_table, bt_stride, batch);
+                     cu_tokens, start_pos, block_table, bt_stride, batch,
+                     int32_t(pool->n_large * k.per_large - 1));
   return hip_status();
 }
 
@@ -1020,7 +1111,8 @@ int64_t jenga_decode_workspace_bytes(const jenga_pool* pool, int32_t kind, int32
 }
 
 int jenga_paged_decode_partial(const jenga_pool* pool, int32_t kind, int32_t layer, const void* q,
-                               int32_t n_q_heads, const int32_t* block_table, int32_t bt_stride,
+                               int32_t n_q_heads, const void* k_new, const void* v_new,
+                               const int32_t* block_table, int32_t bt_stride,
                                const int32_t* seq_lens, int32_t batch, int32_t max_seq_len,
                                int32_t window, float scale, int32_t pages_per_split, void* workspace,
                                int64_t workspace_bytes, jenga_stream stream) {
@@ -1033,6 +1125,9 @@ int jenga_paged_decode_partial(const jenga_pool* pool, int32_t kind, int32_t lay
     return JENGA_ERR_INVALID;
   if (int64_t(bt_stride) * k.desc.tokens_per_page < max_seq_len) return JENGA_ERR_INVALID;
   if (!aligned16(q)) return JENGA_ERR_ALIGN;
+  if ((k_new == nullptr) != (v_new == nullptr)) return JENGA_ERR_INVALID;
+  if (k_new && k.desc.type != JENGA_FULL && k.desc.type != JENGA_WINDOW) return JENGA_ERR_INVALID;
+  if (k_new && (!aligned16(k_new) || !aligned16(v_new))) return JENGA_ERR_ALIGN;
   float *acc = nullptr, *ml = nullptr;
   rc = split_ws(g, workspace, workspace_bytes, &acc, &ml);
   if (rc != JENGA_OK) return rc;
@@ -1047,6 +1142,7 @@ int jenga_paged_decode_partial(const jenga_pool* pool, int32_t kind, int32_t lay
   p.t_log2 = k.t_log2;
   p.n_kv_heads = k.desc.n_kv_heads;
   p.n_q_heads = n_q_heads;
+  p.max_page_id = int32_t(pool->n_large * k.per_large - 1);
   p.q = q;
   p.block_table = block_table;
   p.bt_stride = bt_stride;
@@ -1057,6 +1153,8 @@ int jenga_paged_decode_partial(const jenga_pool* pool, int32_t kind, int32_t lay
   p.scale_log2 = scale * 1.4426950408889634f;
   p.chunk_tiles = g.chunk_tiles;
   p.min_chunk_tiles = g.min_chunk_tiles;
+  p.k_new = k_new;
+  p.v_new = v_new;
   p.ws_acc = acc;
   p.ws_ml = ml;
   const int n_part = launch_partitions(g);
@@ -1095,13 +1193,14 @@ int jenga_splitk_reduce(const jenga_pool* pool, int32_t kind, int32_t n_q_heads,
 }
 
 int jenga_paged_decode(const jenga_pool* pool, int32_t kind, int32_t layer, const void* q,
-                       int32_t n_q_heads, const int32_t* block_table, int32_t bt_stride,
+                       int32_t n_q_heads, const void* k_new, const void* v_new,
+                       const int32_t* block_table, int32_t bt_stride,
                        const int32_t* seq_lens, int32_t batch, int32_t max_seq_len, int32_t window,
                        float scale, int32_t pages_per_split, void* workspace, int64_t workspace_bytes,
                        float* out, jenga_stream stream) {
   if (!out) return JENGA_ERR_INVALID;
   if (!aligned16(out)) return JENGA_ERR_ALIGN;
-  const int rc = jenga_paged_decode_partial(pool, kind, layer, q, n_q_heads, block_table, bt_stride,
+  const int rc = jenga_paged_decode_partial(pool, kind, layer, q, n_q_heads, k_new, v_new, block_table, bt_stride,
                                             seq_lens, batch, max_seq_len, window, scale,
                                             pages_per_split, workspace, workspace_bytes, stream);
   if (rc != JENGA_OK) return rc;

@@ -39,11 +39,12 @@ class DecodeRunner:
     def __init__(self, cfg: ModelCfg, seed: int, device: str = "cuda:0",
                  ctx: Optional[np.ndarray] = None, pages_per_split: int = 0,
                  script_seed: Optional[int] = None, step_budget: int = 0,
-                 pool_u8: Optional[torch.Tensor] = None):
+                 pool_u8: Optional[torch.Tensor] = None, fuse_append: bool = True):
         if not torch.cuda.is_available():
             raise RuntimeError("DecodeRunner needs a GPU")
         self.cfg, self.seed, self.device = cfg, seed, torch.device(device)
         self.pages_per_split = pages_per_split
+        self.fuse_append = fuse_append            # append inside the decode kernel, or as its own launch
         self.script_seed = seed if script_seed is None else script_seed   # placement only
         self.ctx = scripts.sample_ctx(cfg, seed) if ctx is None else np.asarray(ctx, dtype=np.int64)
         self.descs = kind_descs(cfg)
@@ -191,17 +192,20 @@ class DecodeRunner:
     def run_layer(self, k: int, layer: int, split: bool = False, events=None) -> None:
         kd = self.cfg.kinds[k]
         q, k_new, v_new = self.inputs[(k, layer)]
-        if k_new is not None:
+        fused = self.fuse_append and k_new is not None
+        if k_new is not None and not fused:
             self.pool.kv_append(k, layer, k_new, v_new, self.tables[k], self.seq_lens[k])
+        kn, vn = (k_new, v_new) if fused else (None, None)
         if not split and events is None:
             self.pool.paged_decode(k, layer, q, self.tables[k], self.seq_lens[k], self.max_len[k],
                                    kd.window, self.scale(k), self.workspace[k], self.out[(k, layer)],
-                                   self.pages_per_split)
+                                   self.pages_per_split, kn, vn)
             return
         if events is not None:
             events[0].record()
         self.pool.paged_decode_partial(k, layer, q, self.tables[k], self.seq_lens[k], self.max_len[k],
-                                       kd.window, self.scale(k), self.workspace[k], self.pages_per_split)
+                                       kd.window, self.scale(k), self.workspace[k], self.pages_per_split,
+                                       kn, vn)
         if events is not None:
             events[1].record()
         self.pool.splitk_reduce(k, kd.n_q_heads, self.seq_lens[k], self.max_len[k], kd.window,

@@ -241,6 +241,30 @@ def test_result_does_not_depend_on_physical_placement():
         assert torch.equal(outs[0][key], outs[1][key])
 
 
+@pytest.mark.parametrize("dtype,D,G,T,window", [("bf16", 256, 2, 16, 0), ("bf16", 128, 4, 16, 70), ("f32", 64, 2, 16, 0),
+                                                 ("bf16", 128, 8, 16, 0), ("bf16", 64, 2, 32, 40), ("f32", 256, 1, 16, 0)])
+def test_append_inside_decode_equals_separate_append(dtype, D, G, T, window):
+    """Appending inside the decode kernel gives the same pool bytes and the same outputs as
+    jenga_kv_append followed by decode."""
+    print(f"[case] fused append {dtype} D={D} G={G} T={T} W={window}", flush=True)
+    cfg = custom_cfg(dtype, D, 2 * G, 2, WINDOW if window else FULL, window=window, hi=700, T=T, batch=5)
+    ctx = scripts.sample_ctx(cfg, 61)
+    ctx[0], ctx[1] = 0, 15          # a first token, and a token that fills its page
+    results = []
+    for fuse in (False, True):
+        r = _runner(cfg, 61, ctx=ctx, fuse_append=fuse)
+        prepare(r)
+        r.device_step()
+        check_against_oracle(r, f"{cfg.name}/fuse={fuse}")
+        check_append_landed(r)
+        torch.cuda.synchronize()
+        results.append(({key: v.cpu().clone() for key, v in r.out.items()}, r.pool_u8.cpu().clone()))
+        r.close()
+    for key in results[0][0]:
+        assert torch.equal(results[0][0][key], results[1][0][key])
+    assert torch.equal(results[0][1], results[1][1])
+
+
 def test_partial_plus_reduce_equals_fused_entry_point():
     cfg = custom_cfg("bf16", 128, 8, 2, WINDOW, window=200, lo=100, hi=1500, n_layers=1)
     r = _runner(cfg, 31, pages_per_split=4)
@@ -323,6 +347,33 @@ def test_prefix_sharing_reads_shared_pages():
     r.device_step()
     check_against_oracle(r, "prefix-sharing")
     r.close()
+
+
+def test_bad_table_entries_are_clamped_not_followed():
+    """Entries of the visible range that are negative or past the pool are a caller error; the
+    kernels clamp them (reads) or skip them (writes), so other requests are unaffected."""
+    cfg = custom_cfg("bf16", 128, 8, 2, FULL, lo=100, hi=600, n_layers=1, batch=4)
+    for fuse in (True, False):
+        r = _runner(cfg, 17, fuse_append=fuse)
+        prepare(r)
+        before = r.pool_u8.clone()
+        tab = r.tables[0].clone()
+        tab[1, :] = -1
+        tab[2, 0] = 2 ** 30
+        tab[2, int(r.seq_lens_host[0][2] - 1) // 16] = 2 ** 30      # the page the append would write
+        r.tables[0] = tab
+        r.device_step()
+        torch.cuda.synchronize()
+        got = r.out[(0, 0)].cpu().double().numpy()
+        q = r.inputs[(0, 0)][0].cpu().double().numpy()
+        for b in (0, 3):
+            K, V = r.contiguous_kv(0, 0, b)
+            want = decode_attention_one(q[b], K.double().numpy(), V.double().numpy(), r.scale(0), 0)
+            assert np.abs(got[b] - want).max() <= TOL_BF16_ABS
+        # nothing was written for the two requests with bad tables: only requests 0 and 3 appended
+        changed = (r.pool_u8 != before).sum().item()
+        assert changed <= 2 * 2 * 2 * 128 * 2
+        r.close()
 
 
 def test_device_entry_points_reject_bad_arguments():
