@@ -236,7 +236,7 @@ struct PageIds {
   int n_pages;
   int lane;
   int max_id;
-  int reg[2];
+  int reg0, reg1;       // two scalars, not an array: an indexed member would live in scratch memory
 
   // A table entry that is negative or past the pool (a caller error: pages of the visible
   // range must be resident) is clamped, so the kernel reads wrong data rather than faulting.
@@ -246,8 +246,8 @@ struct PageIds {
   }
   __device__ __forceinline__ void init(const int32_t* r, int n, int l, int max_page_id) {
     row = r; n_pages = n; lane = l; max_id = max_page_id;
-    reg[0] = fetch(0);
-    reg[1] = fetch(kWave);
+    reg0 = fetch(0);
+    reg1 = fetch(kWave);
   }
   // true when the table entry itself is a page of the pool (used before writing into it)
   __device__ __forceinline__ bool writable(int page_rel) const {
@@ -255,14 +255,15 @@ struct PageIds {
     return raw >= 0 && raw <= max_id;
   }
   __device__ __forceinline__ int get(int page_rel) const {
-    const int r = (page_rel & kWave) ? reg[1] : reg[0];
+    const int r = (page_rel & kWave) ? reg1 : reg0;
     return __builtin_amdgcn_readlane(r, page_rel & (kWave - 1));
   }
   // Call after the K stream has issued the loads of a tile starting at page_rel.
   __device__ __forceinline__ void k_stream_at(int page_rel) {
     if ((page_rel & (kWave - 1)) == 0 && page_rel > 0) {
-      if (page_rel & kWave) reg[0] = fetch(page_rel + kWave);
-      else reg[1] = fetch(page_rel + kWave);
+      const int next = fetch(page_rel + kWave);
+      if (page_rel & kWave) reg0 = next;
+      else reg1 = next;
     }
   }
 };
@@ -316,9 +317,8 @@ struct QuadEngine {
   static constexpr int kLdsFloats = 2 * PPT * T * G;   // softmax weights of a tile, double buffered
   static_assert(KCH >= 2 && KCH <= 8, "row size");
 
-  __device__ static void run(const DecodeParams& p, int lane, int b, int kvh, int L, int tile0,
+  __device__ __forceinline__ static void run(const DecodeParams& p, int lane, int b, int kvh, int L, int tile0,
                              int n_tiles, int append_tile, int64_t slot, float* lds) {
-    const bool append = append_tile >= 0;
     int lo_tok, p_lo, p_hi;
     visible_pages(L, p.window, 4, &lo_tok, &p_lo, &p_hi);
     const int page0 = p_lo + tile0 * PPT;
@@ -354,19 +354,6 @@ struct QuadEngine {
       for (int j = 0; j < EPL; ++j) acc[g][j] = 0.f;
     }
 
-    // Fused append: the wavefront whose chunk holds the tile of the newest token (position
-    // L - 1) takes that token's rows from k_new / v_new instead of the pool, and stores them
-    // into the page.
-    u32x4 k_app[KCH], v_app;
-    if (append) {
-      const char* kn = static_cast<const char*>(p.k_new) + (int64_t(b) * p.n_kv_heads + kvh) * ROW;
-      const char* vn = static_cast<const char*>(p.v_new) + (int64_t(b) * p.n_kv_heads + kvh) * ROW;
-#pragma unroll
-      for (int c = 0; c < KCH; ++c)
-        k_app[c] = *reinterpret_cast<const u32x4*>(kn + c * 64 + (lane & 3) * 16);
-      v_app = *reinterpret_cast<const u32x4*>(vn + (lane % LPT) * 16);
-    }
-
     auto load_pages = [&](int tile, unsigned voff, int step, u32x4* buf) {
 #pragma unroll
       for (int pp = 0; pp < PPT; ++pp) {
@@ -398,7 +385,18 @@ struct QuadEngine {
     auto step = [&](int tile, u32x4* kbuf, u32x4* vbuf, u32x4* v_next) {
       if (tile + 1 < n_tiles) load_pages(tile + 1, v_voff, 1024, v_next);
 
+      // Fused append: the wavefront whose chunk holds the tile of the newest token (position
+      // L - 1) takes that token's rows from k_new / v_new instead of the pool and stores them
+      // into the page.  The rows are fetched here, once per (request, head), rather than held
+      // in registers through the whole loop.
       if (tile == append_tile) {
+        const char* kn = static_cast<const char*>(p.k_new) + (int64_t(b) * p.n_kv_heads + kvh) * ROW;
+        const char* vn = static_cast<const char*>(p.v_new) + (int64_t(b) * p.n_kv_heads + kvh) * ROW;
+        u32x4 k_app[KCH];
+#pragma unroll
+        for (int c = 0; c < KCH; ++c)
+          k_app[c] = *reinterpret_cast<const u32x4*>(kn + c * 64 + (lane & 3) * 16);
+        const u32x4 v_app = *reinterpret_cast<const u32x4*>(vn + (lane % LPT) * 16);
         const int pos = L - 1;
         const int page_rel = (pos >> 4) - page0;
         const int pp_new = page_rel - tile * PPT;           // page of the tile that holds the new token
@@ -544,9 +542,8 @@ struct RowEngine {
   static constexpr int kTileLog2 = TT == 8 ? 3 : TT == 16 ? 4 : TT == 32 ? 5 : 6;
   static constexpr int kLdsFloats = 0;
 
-  __device__ static void run(const DecodeParams& p, int lane, int b, int kvh, int L, int tile0,
+  __device__ __forceinline__ static void run(const DecodeParams& p, int lane, int b, int kvh, int L, int tile0,
                              int n_tiles, int append_tile, int64_t slot, float*) {
-    const bool append = append_tile >= 0;
     int lo_tok, p_lo, p_hi;
     visible_pages(L, p.window, p.t_log2, &lo_tok, &p_lo, &p_hi);
     const int t_mask = (1 << p.t_log2) - 1;
@@ -596,21 +593,17 @@ struct RowEngine {
       }
     };
 
-    // fused append (see the quad engine): rows of the token at L - 1 come from k_new / v_new
-    u32x4 k_app = u32x4{0, 0, 0, 0}, v_app = u32x4{0, 0, 0, 0};
-    if (append) {
-      const int64_t off = (int64_t(b) * p.n_kv_heads + kvh) * ROW + sub * 16;
-      k_app = *reinterpret_cast<const u32x4*>(static_cast<const char*>(p.k_new) + off);
-      v_app = *reinterpret_cast<const u32x4*>(static_cast<const char*>(p.v_new) + off);
-    }
-
     u32x4 kbuf[NL], vbuf[NL];
     load_tile(0, 0, kbuf);
 
     for (int tile = 0; tile < n_tiles; ++tile) {
       load_tile(tile, p.v_offset, vbuf);
 
+      // fused append (see the quad engine): rows of the token at L - 1 come from k_new / v_new
       if (tile == append_tile) {
+        const int64_t off = (int64_t(b) * p.n_kv_heads + kvh) * ROW + sub * 16;
+        const u32x4 k_app = *reinterpret_cast<const u32x4*>(static_cast<const char*>(p.k_new) + off);
+        const u32x4 v_app = *reinterpret_cast<const u32x4*>(static_cast<const char*>(p.v_new) + off);
         const int pos = L - 1;
         const int page_rel = (pos >> p.t_log2) - page0;
         bool mine = false;

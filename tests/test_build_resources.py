@@ -1,0 +1,35 @@
+"""Build-time guard: no decode kernel may use scratch (stack) memory.
+
+A struct member indexed at run time once pushed the page-id registers into scratch memory and
+cost the G = 4 kernels 40 % of their speed without failing any parity test; this compiles the
+kernels to assembly (no GPU needed) and reads the resource metadata hipcc emits."""
+import os
+import re
+import shutil
+import subprocess
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.mark.skipif(shutil.which("hipcc") is None and not os.path.exists("/opt/rocm/bin/hipcc"), reason="needs hipcc")
+def test_decode_kernels_use_no_scratch_memory(tmp_path):
+    from paper_2503_18292_amd import build
+    src = os.path.join(ROOT, "paper_2503_18292_amd", "csrc", "kernels.hip")
+    out = str(tmp_path / "kernels.s")
+    cmd = [build.hipcc(), "-O3", "-std=c++17", "--offload-arch=gfx950", "--cuda-device-only", "-S",
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-I", os.path.join(ROOT, "include"), "-I", os.path.dirname(src), src, "-o", out]
+    subprocess.run(cmd, check=True, capture_output=True, text=True)
+    txt = open(out).read()
+    seen = 0
+    for m in re.finditer(r"- \.agpr_count:.*?\.wavefront_size", txt, re.S):
+        blk = m.group(0)
+        name = re.search(r"\.name:\s+(\S+)", blk).group(1)
+        if "decode_partial_kernel" not in name:
+            continue
+        seen += 1
+        scratch = int(re.search(r"\.private_segment_fixed_size:\s+(\d+)", blk).group(1))
+        assert scratch == 0, f"{name} uses {scratch} bytes of scratch memory per lane"
+    assert seen >= 30
