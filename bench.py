@@ -27,8 +27,9 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
 # HBM traffic of one decode_partial launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
 # each scaled by what the same counter reads for a plain copy of known size (summary and
 # commands: profiles/decode_kernels_gemma2_9b_hbm_traffic.md): fetched bytes are 1.007 x the
-# algorithmic K/V bytes, written bytes 3.18e6 per launch.  Only known for the default workload.
-MEASURED_TRAFFIC = {"gemma2_9b": {"fetch_over_algorithmic": 1.007, "write_bytes": 3.18e6}}
+# algorithmic K/V bytes, written bytes 3.70e6 per launch (split-K records and the appended rows).
+# Only known for the default workload.
+MEASURED_TRAFFIC = {"gemma2_9b": {"fetch_over_algorithmic": 1.007, "write_bytes": 3.70e6}}
 
 
 def parse():
