@@ -1,0 +1,87 @@
+"""GPU parity at the limits of what the kernels accept: the largest batch, a batch that needs
+several rounds of the per-block length scan, one very long request next to very short ones,
+and lengths above the stated maximum (clamped by the kernels)."""
+import numpy as np
+import pytest
+import torch
+
+from workloads.configs import FULL, WINDOW
+
+from test_gpu_parity import _runner, check_against_oracle, check_append_landed, custom_cfg, prepare
+
+pytestmark = pytest.mark.gpu
+
+MAX_BATCH = 1024      # stated in the header of the decode entry points
+
+
+@pytest.mark.parametrize("batch,T,dtype,D,G,window", [
+    (MAX_BATCH, 16, "bf16", 128, 4, 0),      # quad engine
+    (MAX_BATCH, 32, "f32", 64, 2, 40),       # row engine, sliding window
+    (65, 16, "bf16", 256, 2, 0),             # one request past a full round of the length scan
+    (200, 16, "f32", 64, 1, 0),
+])
+def test_large_batches(batch, T, dtype, D, G, window):
+    print(f"[case] batch={batch} T={T} {dtype} D={D} G={G} W={window}", flush=True)
+    typ = WINDOW if window else FULL
+    cfg = custom_cfg(dtype, D, 2 * G, 2, typ, window=window, batch=batch, lo=0, hi=90, n_layers=1, T=T)
+    r = _runner(cfg, 77 + batch)
+    prepare(r)
+    r.device_step()
+    check_against_oracle(r, cfg.name)
+    check_append_landed(r)
+    r.close()
+
+
+def test_batch_above_the_limit_is_refused():
+    import paper_2503_18292_amd as J
+    cfg = custom_cfg("bf16", 128, 4, 2, FULL, batch=2, n_layers=1)
+    r = _runner(cfg, 1)
+    prepare(r)
+    B = MAX_BATCH + 1
+    q = torch.zeros(B, 4, 128, dtype=torch.bfloat16, device="cuda")
+    table = torch.zeros(B, r.tables[0].shape[1], dtype=torch.int32, device="cuda")
+    lens = torch.ones(B, dtype=torch.int32, device="cuda")
+    out = torch.empty(B, 4, 128, dtype=torch.float32, device="cuda")
+    ws = torch.empty(1 << 22, dtype=torch.float32, device="cuda")
+    with pytest.raises(J.JengaError) as e:
+        r.pool.paged_decode(0, 0, q, table, lens, r.max_len[0], 0, 0.1, ws, out)
+    assert e.value.status == -6      # JENGA_ERR_UNSUPPORTED
+    torch.cuda.synchronize()
+    r.close()
+
+
+@pytest.mark.parametrize("dtype,D,G,window", [("bf16", 128, 4, 0), ("bf16", 256, 2, 0), ("bf16", 128, 4, 1024)])
+def test_one_very_long_request_among_short_ones(dtype, D, G, window):
+    """131072 tokens (the longest length of the synthetic workloads) next to 1- and 6-token
+    requests: almost every wavefront works on the long request, a few segments are tiny."""
+    print(f"[case] long request {dtype} D={D} G={G} W={window}", flush=True)
+    typ = WINDOW if window else FULL
+    cfg = custom_cfg(dtype, D, 2 * G, 2, typ, window=window, batch=3, n_layers=1)
+    r = _runner(cfg, 9, ctx=np.array([0, 131071, 5]))
+    prepare(r)
+    r.device_step()
+    check_against_oracle(r, cfg.name)
+    check_append_landed(r)
+    r.close()
+
+
+def test_lengths_above_max_seq_len_are_clamped():
+    """A length above max_seq_len is treated as max_seq_len: the result is that of the clamped
+    length, and nothing past the table's width is read."""
+    cfg = custom_cfg("bf16", 128, 4, 2, FULL, n_layers=1)
+    ctx = np.array([100, 37, 63])
+    r = _runner(cfg, 2, ctx=ctx)
+    prepare(r)
+    k, layer = r.schedule[0]
+    q = r.inputs[(k, layer)][0]
+    cap = 64                                           # a page boundary below two of the lengths
+    lens_clamped = torch.minimum(r.seq_lens[k], torch.tensor(cap, dtype=torch.int32, device="cuda"))
+    want = torch.empty_like(r.out[(k, layer)])
+    got = torch.empty_like(want)
+    table = r.tables[k][:, :cap // 16].contiguous()
+    r.pool.kv_append(k, layer, *r.inputs[(k, layer)][1:], r.tables[k], r.seq_lens[k])
+    r.pool.paged_decode(k, layer, q, table, lens_clamped, cap, 0, r.scale(k), r.workspace[k], want)
+    r.pool.paged_decode(k, layer, q, table, r.seq_lens[k], cap, 0, r.scale(k), r.workspace[k], got)
+    torch.cuda.synchronize()
+    assert torch.equal(got.cpu(), want.cpu())
+    r.close()
