@@ -804,20 +804,35 @@ __global__ __launch_bounds__(kWave) void splitk_reduce_kernel(
   const int c_lo = S / C;
   const int c_hi = (S + tiles_b - 1) / C;
   const int64_t seg = int64_t(b) * n_kv_heads + kvh;
-  float m_star = kNegBig;
-  for (int c = c_lo; c <= c_hi; ++c) m_star = fmaxf(m_star, ws_ml[((seg + c) * G + g) * 2]);
+  // Four records at a time, all their loads issued before any is used (a segment rarely has
+  // more than four); the running maximum is carried from one group to the next.
+  float m_star = kNegBig, l_star = 0.f;
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-  float l_star = 0.f;
-  for (int c = c_lo; c <= c_hi; ++c) {
-    const int64_t rec = (seg + c) * G + g;
-    const float2 ml = *reinterpret_cast<const float2*>(ws_ml + rec * 2);
-    const float w = __builtin_amdgcn_exp2f(ml.x - m_star);
-    l_star = fmaf(ml.y, w, l_star);
-    if (owner) {
-      const float4 a = *(reinterpret_cast<const float4*>(ws_acc + rec * D) + lane);
-      acc.x = fmaf(a.x, w, acc.x); acc.y = fmaf(a.y, w, acc.y);
-      acc.z = fmaf(a.z, w, acc.z); acc.w = fmaf(a.w, w, acc.w);
+  for (int c0 = c_lo; c0 <= c_hi; c0 += 4) {
+    float2 ml[4];
+    float4 a[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int64_t rec = (seg + min(c0 + i, c_hi)) * G + g;
+      ml[i] = *reinterpret_cast<const float2*>(ws_ml + rec * 2);
+      a[i] = owner ? *(reinterpret_cast<const float4*>(ws_acc + rec * D) + lane) : make_float4(0.f, 0.f, 0.f, 0.f);
     }
+    float m_new = m_star;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (c0 + i <= c_hi) m_new = fmaxf(m_new, ml[i].x);
+    const float keep = __builtin_amdgcn_exp2f(m_star - m_new);
+    l_star *= keep;
+    acc.x *= keep; acc.y *= keep; acc.z *= keep; acc.w *= keep;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      if (c0 + i > c_hi) continue;
+      const float w = __builtin_amdgcn_exp2f(ml[i].x - m_new);
+      l_star = fmaf(ml[i].y, w, l_star);
+      acc.x = fmaf(a[i].x, w, acc.x); acc.y = fmaf(a[i].y, w, acc.y);
+      acc.z = fmaf(a[i].z, w, acc.z); acc.w = fmaf(a[i].w, w, acc.w);
+    }
+    m_star = m_new;
   }
   const float inv = l_star > 0.f ? 1.0f / l_star : 0.f;
   if (owner) *dst = make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv);
