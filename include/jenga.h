@@ -253,9 +253,10 @@ int jenga_kv_write_range(const jenga_pool* pool, int32_t kind, int32_t layer,
 
 /* Upper bound of the number of work partitions (wavefront tasks) the decode kernels use for
  * these arguments.  The visible K/V of all (request, KV head) pairs, cut into tiles and laid
- * end to end, is divided into equal partitions; pages_per_split = 0 lets the library take one
- * partition per wavefront the device can hold at once (every wavefront then streams the same
- * number of bytes whatever the mix of lengths), pages_per_split > 0 fixes the partition size.
+ * end to end (each pair charged a few extra units for the cost of starting on it), is divided
+ * into equal partitions; pages_per_split = 0 lets the library take one partition per
+ * wavefront the device can hold at once (every wavefront then has the same amount of work
+ * whatever the mix of lengths), pages_per_split > 0 fixes the partition size.
  * Returns the bound (>= 1) or a negative status. */
 int jenga_decode_num_partitions(const jenga_pool* pool, int32_t kind, int32_t n_q_heads,
                                 int32_t batch, int32_t max_seq_len, int32_t window,
@@ -285,7 +286,7 @@ int64_t jenga_decode_workspace_bytes(const jenga_pool* pool, int32_t kind, int32
  *   seq_lens     device int32 [batch], each <= max_seq_len (larger ones are clamped)
  *   max_seq_len  host upper bound of seq_lens; sizes the grid; bt_stride * T >= max_seq_len
  *   window       0: none.  Pass the kind's window for WINDOW kinds.
- *   pages_per_split  0: automatic (balanced partitions); else pages of K/V per partition
+ *   pages_per_split  0: automatic (balanced partitions); else the partition size in pages of K/V
  *   workspace    device, >= jenga_decode_workspace_bytes(...), 16-byte aligned, caller-owned;
  *                holds per-partition (max, sum, accumulator) between the two kernels
  * Runs the partial kernel and the split-K reduction on `stream`.
