@@ -1243,6 +1243,7 @@ DecodeFn pick_g(bool mat, bool quad, int G) {
           default: break;
         }
       }
+      if (G == 16) return decode_partial_kernel<MatEngine<D, 16>>;
       return decode_partial_kernel<MatEngine<D, 8>>;
     }
   }
@@ -1321,7 +1322,8 @@ int decode_geometry(const jenga_pool* pool, int32_t kind, int32_t n_q_heads, int
   if (batch > kMaxBatch) return JENGA_ERR_UNSUPPORTED;
   if (n_q_heads % k.desc.n_kv_heads != 0) return JENGA_ERR_INVALID;
   const int G = n_q_heads / k.desc.n_kv_heads;
-  if (G != 1 && G != 2 && G != 4 && G != 8) return JENGA_ERR_UNSUPPORTED;
+  if (G != 1 && G != 2 && G != 4 && G != 8 && G != 16) return JENGA_ERR_UNSUPPORTED;
+  if (G == 16 && !(k.desc.dtype == JENGA_BF16 && k.t_log2 == 4)) return JENGA_ERR_UNSUPPORTED;
   const int row = k.desc.head_dim * k.elem_bytes;
   const int T = k.desc.tokens_per_page;
   out->kind = &k;
@@ -1329,7 +1331,7 @@ int decode_geometry(const jenga_pool* pool, int32_t kind, int32_t n_q_heads, int
   // 16-token pages: bf16 K/V goes to the matrix-core engine, except 256-element rows with up to 4
   // query heads per KV head, where the quad engine measures 0.7 % faster; fp32 K/V goes to the
   // quad engine up to 4 heads per KV head.  Everything else takes the general engine.
-  out->mat = k.t_log2 == 4 && k.desc.dtype == JENGA_BF16 && (row <= 256 || G == 8);
+  out->mat = k.t_log2 == 4 && k.desc.dtype == JENGA_BF16 && (row <= 256 || G >= 8);
   out->quad = k.t_log2 == 4 && G <= 4 && row <= 512;
   const bool paged16 = out->mat || out->quad;      // tiles of 8 KiB K + 8 KiB V in whole pages
   const int tile_tokens = paged16 ? (8 / (row / 64)) * 16 : 8 * (kWave / (row / 16));

@@ -107,6 +107,7 @@ def custom_cfg(dtype, D, Hq, Hkv, typ, window=0, batch=3, lo=1, hi=700, n_layers
 
 
 SHAPES = [(dt, D, G) for dt in ("bf16", "f32") for D in (64, 128, 256) for G in (1, 2, 4, 8)]
+SHAPES += [("bf16", D, 16) for D in (64, 128, 256)]      # 16 heads per KV head: matrix-core engine only
 
 
 @pytest.mark.parametrize("dtype,D,G", SHAPES)
@@ -136,6 +137,22 @@ def test_other_page_sizes(T, dtype, D, G, window):
         check_against_oracle(r, f"{cfg.name}/T{T}/pps{pps}")
         check_append_landed(r)
         r.close()
+
+
+@pytest.mark.parametrize("D,G,window,pps", [(128, 8, 0, 0), (128, 8, 200, 2), (128, 16, 0, 6), (64, 8, 70, 0), (64, 4, 0, 4),
+                                            (256, 8, 0, 0), (256, 16, 33, 1), (128, 1, 0, 2), (64, 16, 0, 0)])
+def test_matrix_core_engine_shapes(D, G, window, pps):
+    """bf16 K/V in 16-token pages on the matrix-core engine: ragged lengths from one token to
+    many tiles, windows that start inside a page, partitions that cut inside a tile pair."""
+    print(f"[case] matrix-core D={D} G={G} W={window} pps={pps}", flush=True)
+    cfg = custom_cfg("bf16", D, 2 * G, 2, WINDOW if window else FULL, window=window, batch=7, lo=0, hi=1300)
+    r = _runner(cfg, 500 + D + G, pages_per_split=pps,
+                ctx=np.array([0, 1, 15, 16, 31, 1299, 640]))
+    prepare(r)
+    r.device_step()
+    check_against_oracle(r, cfg.name)
+    check_append_landed(r)
+    r.close()
 
 
 @pytest.mark.parametrize("dtype,D,G,W", [("bf16", 256, 2, 100), ("bf16", 128, 4, 64), ("bf16", 64, 1, 33),

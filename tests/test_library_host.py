@@ -224,6 +224,11 @@ def test_partition_geometry_and_workspace_queries():
     with pytest.raises(J.JengaError) as e:
         lib.decode_workspace_bytes(0, 24, 64, 8193)      # 24 query heads over 8 KV heads: G = 3
     assert e.value.status == -6
+    assert lib.decode_workspace_bytes(0, 128, 64, 8193) > 0    # G = 16: bf16 K/V in 16-token pages only
+    tiny_lib = make_library(configs.tiny(), 4)
+    with pytest.raises(J.JengaError) as e:
+        tiny_lib.decode_workspace_bytes(0, 32, 4, 256)       # fp32 K/V, 2 KV heads: G = 16
+    assert e.value.status == -6
     with pytest.raises(J.JengaError) as e:
         lib.decode_workspace_bytes(0, 16, 5000, 8193)    # batch beyond the kernels' limit
     assert e.value.status == -6
