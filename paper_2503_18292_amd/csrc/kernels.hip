@@ -7,11 +7,15 @@
 //                          of a KV head share every load; one wavefront per work partition
 //   splitk_reduce_kernel   log-sum-exp merge of the partitions of each (request, query head)
 //
-// Decode attention is a bandwidth-bound matrix-vector product (G flop per byte of bf16 K/V),
-// so no matrix-core instructions are used.  What decides the speed is (1) that every
-// wavefront always has KiB-sized loads in flight, (2) that no wavefront idles while others
-// still work (work is cut into equal pieces, not into per-request pieces), and (3) few
-// vector-ALU instructions per byte.
+// Decode attention is bandwidth-bound (G flop per byte of bf16 K/V).  What decides the speed
+// is (1) that every wavefront always has KiB-sized loads in flight, (2) that no wavefront
+// idles while others still work (work is cut into equal pieces, not into per-request pieces),
+// and (3) that the arithmetic stays out of the way of the loads.  Three engines share the
+// front end: the matrix-core engine (bf16 K/V, 16-token pages: both products of a page are
+// small dense contractions and go through MFMA, which leaves the vector ALUs almost idle and
+// is what keeps 8 and 16 heads per KV head at the HBM rate), the quad engine (16-token pages
+// on the vector ALUs: fp32 K/V, and 256-element bf16 rows with few heads, where it measures
+// slightly faster), and the general row engine (other page sizes).
 //
 // The kernel view of the pool is the one of paper Sec. 4.2: a start pointer (pool base +
 // layer offset), a page stride (the kind's small-page size) and page ids (the kind's block
@@ -547,8 +551,8 @@ struct QuadEngine {
 // K and V are read alike: a token's row is LPT lanes x 16 bytes, one wave-wide load covers
 // TPL = 64 / LPT consecutive tokens (1 KiB, contiguous in the page).  Every partial dot
 // product is summed over LPT lanes, so this engine spends several times more vector-ALU
-// work per byte than the one above; it covers what that one is not built for (pages of 8,
-// 32, 64 or 128 tokens, 8 query heads per KV head, 1 KiB rows).  Each group of LPT lanes runs
+// work per byte than the one above; it covers what the other two are not built for (pages of
+// 8, 32, 64 or 128 tokens; fp32 K/V with 8 query heads per KV head or 1 KiB rows).  Each group of LPT lanes runs
 // its own online softmax over the tokens it sees; the groups are merged once at the end.
 template <typename E_, int D_, int G_>
 struct RowEngine {
