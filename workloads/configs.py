@@ -88,6 +88,20 @@ def tiny() -> ModelCfg:
     )
 
 
+def mini_bf16() -> ModelCfg:
+    """A seconds-sized bf16 case for smoke checks: one full-attention kind with 256-element rows
+    and 2 query heads per KV head, one sliding-window kind with 128-element rows and 4."""
+    return ModelCfg(
+        name="mini_bf16",
+        kinds=[
+            KindCfg("full", FULL, "bf16", 2, 4, 2, 256, 16),
+            KindCfg("window96", WINDOW, "bf16", 3, 8, 2, 128, 16, window=96),
+        ],
+        batch=5, ctx=LengthDist("uniform", 1, 700), value_sigma=0.5,
+        build_chunk=32, n_dummy=2, dummy_ctx=(1, 96),
+    )
+
+
 def gemma2_9b() -> ModelCfg:
     return ModelCfg(
         name="gemma2_9b",
