@@ -322,9 +322,11 @@ def main():
         k_ms, k_bytes, n_launch = 0.0, 0.0, 0
         per_kind_ms = {k: 0.0 for k in r.attn_kinds}
         per_kind_bytes = {k: 0.0 for k in r.attn_kinds}
+        launch_ms = []
         for i in range(args.steps):
             for (k, layer), (e0, e1) in ev[i].items():
                 ms = e0.elapsed_time(e1)
+                launch_ms.append(ms)
                 k_ms += ms
                 k_bytes += layer_bytes[i][k]
                 per_kind_ms[k] += ms
@@ -334,6 +336,8 @@ def main():
         roof.update({
             "achieved": round(achieved, 1), "frac": round(achieved / HBM_PEAK_GBS, 4),
             "launches": n_launch, "avg_launch_us": round(k_ms / n_launch * 1e3, 2),
+            "median_launch_us": round(float(np.median(launch_ms)) * 1e3, 2),
+            "min_launch_us": round(min(launch_ms) * 1e3, 2),
             "ms_per_step_with_events": round(ms_per_step_events, 3),
             "algorithmic_bytes_per_launch": round(k_bytes / n_launch),
             "traffic": (round(MEASURED_TRAFFIC[cfg.name]["fetch_over_algorithmic"] * k_bytes / n_launch
