@@ -11,11 +11,11 @@
 // is (1) that every wavefront always has KiB-sized loads in flight, (2) that no wavefront
 // idles while others still work (work is cut into equal pieces, not into per-request pieces),
 // and (3) that the arithmetic stays out of the way of the loads.  Three engines share the
-// front end: the matrix-core engine (bf16 K/V, 16-token pages: both products of a page are
-// small dense contractions and go through MFMA, which leaves the vector ALUs almost idle and
-// is what keeps 8 and 16 heads per KV head at the HBM rate), the quad engine (16-token pages
-// on the vector ALUs: fp32 K/V, and 256-element bf16 rows with few heads, where it measures
-// slightly faster), and the general row engine (other page sizes).
+// front end: the matrix-core engine (bf16 K/V, pages of 16 tokens or more: both products of
+// a 16-token block are small dense contractions and go through MFMA, which leaves the vector
+// ALUs almost idle and is what keeps 8 and 16 heads per KV head at the HBM rate), the quad
+// engine (16-token pages on the vector ALUs: fp32 K/V, and 256-element bf16 rows with few
+// heads, where it measures slightly faster), and the general row engine (the rest).
 //
 // The kernel view of the pool is the one of paper Sec. 4.2: a start pointer (pool base +
 // layer offset), a page stride (the kind's small-page size) and page ids (the kind's block
@@ -551,8 +551,8 @@ struct QuadEngine {
 // K and V are read alike: a token's row is LPT lanes x 16 bytes, one wave-wide load covers
 // TPL = 64 / LPT consecutive tokens (1 KiB, contiguous in the page).  Every partial dot
 // product is summed over LPT lanes, so this engine spends several times more vector-ALU
-// work per byte than the one above; it covers what the other two are not built for (pages of
-// 8, 32, 64 or 128 tokens; fp32 K/V with 8 query heads per KV head or 1 KiB rows).  Each group of LPT lanes runs
+// work per byte than the one above; it covers what the other two are not built for (8-token
+// pages; fp32 K/V in pages other than 16 tokens, with 8 query heads per KV head, or 1 KiB rows).  Each group of LPT lanes runs
 // its own online softmax over the tokens it sees; the groups are merged once at the end.
 template <typename E_, int D_, int G_>
 struct RowEngine {
@@ -735,9 +735,9 @@ struct RowEngine {
   }
 };
 
-// ---- engine for bf16 K/V in 16-token pages: both contractions on the matrix cores --------
+// ---- engine for bf16 K/V in pages of 16 tokens or more: both contractions on the matrix cores
 //
-// The work per page is a small dense contraction, scores = K[16 x D] . Q^T[D x G] and
+// The work per 16-token block is a small dense contraction, scores = K[16 x D] . Q^T[D x G] and
 // out += P[G x 16] . V[16 x D], and the matrix cores take it off the vector ALUs altogether:
 // with 8 heads on every K/V byte those can no longer keep up with HBM (the quad engine would
 // need about 70 vector instructions per KiB), and with fewer heads the loads still issue
@@ -765,15 +765,14 @@ template <int D_, int G_>
 struct MatEngine {
   using E = BF16;
   static constexpr int D = D_, G = G_;
-  static constexpr int T = 16;
+  static constexpr int T = 16;                 // tokens per block; a page holds 1, 2, 4 or 8 blocks
   static constexpr int ROW = D * 2;            // bytes per token row
   static constexpr int KCH = ROW / 64;         // k-steps of the score product == 1 KiB loads per page
-  static constexpr int PPT = 8 / KCH;          // pages per tile (1, 2 or 4)
+  static constexpr int PPT = 8 / KCH;          // blocks per tile (1, 2 or 4)
   static constexpr int NLD = 8;                // 16-byte loads per lane and tile, K and V alike
   static constexpr int LPT = ROW / 16;         // V loads: lanes per token row
   static constexpr int TPL = kWave / LPT;      // V loads: token rows per load
   static constexpr int NBLK = D / 16;          // 16-wide blocks of the output row
-  static constexpr int V_OFF = T * ROW;
   static constexpr int LROW = ROW + 32;        // LDS row pitch: 8 banks further per row
   static constexpr int kTileLog2 = PPT == 1 ? 4 : PPT == 2 ? 5 : 6;
   static constexpr int kLdsFloats = PPT * T * LROW / 4;
@@ -805,11 +804,18 @@ struct MatEngine {
 
   __device__ __forceinline__ static void run(const DecodeParams& p, int lane, int b, int kvh, int L, int tile0,
                              int n_tiles, int append_tile, int64_t slot, float* lds) {
+    // Pages of 16, 32, 64 or 128 tokens are read as runs of 16-token blocks: block q (counted
+    // from the first visible page) lies in page q >> sh at row offset (q & sub_mask) * 16.
+    const int sh = p.t_log2 - 4;
+    const int sub_mask = (1 << sh) - 1;
     int lo_tok, p_lo, p_hi;
-    visible_pages(L, p.window, 4, &lo_tok, &p_lo, &p_hi);
-    const int page0 = p_lo + tile0 * PPT;
-    const int n_pages = min(n_tiles * PPT, p_hi - page0);
-    const int tok0 = page0 * T;
+    visible_pages(L, p.window, p.t_log2, &lo_tok, &p_lo, &p_hi);
+    const int blk0 = tile0 * PPT;                              // first block of the chunk
+    const int page0 = p_lo + (blk0 >> sh);
+    const int off0 = blk0 & sub_mask;                          // its place inside page0
+    const int n_blk = min(n_tiles * PPT, ((p_hi - p_lo) << sh) - blk0);
+    const int n_pages = (off0 + n_blk + sub_mask) >> sh;
+    const int tok0 = ((p_lo << sh) + blk0) * T;
     char* v_lds = reinterpret_cast<char*>(lds);
 
     PageIds ids;
@@ -819,7 +825,7 @@ struct MatEngine {
     const int v_row = lane / LPT;                                        // V loads: row v_row + TPL * c of the page
     const char* kv_base = p.layer_base + int64_t(kvh) * p.head_stride;   // wave-uniform
     const unsigned k_voff = n * ROW + j * 16;                            // A operand of the score product
-    const unsigned v_voff = V_OFF + lane * 16;
+    const unsigned v_voff = p.v_offset + lane * 16;
     const unsigned lds_wr = v_row * LROW + (lane % LPT) * 16;            // this lane's V bytes (+ row offset)
     const unsigned lds_rd = (4 * j + (n >> 2)) * LROW + (n & 3) * 8;     // transposed read (+ page, + block)
 
@@ -842,9 +848,10 @@ struct MatEngine {
     auto load_pages = [&](int tile, unsigned voff, int step, u32x4* buf) {
 #pragma unroll
       for (int pp = 0; pp < PPT; ++pp) {
-        const int page_rel = tile * PPT + pp;
-        if (PPT == 1 || page_rel < n_pages) {
-          const char* pb = kv_base + int64_t(ids.get(page_rel)) * p.small_bytes;
+        const int r = tile * PPT + pp;
+        if (PPT == 1 || r < n_blk) {
+          const int q = off0 + r;
+          const char* pb = kv_base + int64_t(ids.get(q >> sh)) * p.small_bytes + (q & sub_mask) * (T * ROW);
 #pragma unroll
           for (int c = 0; c < KCH; ++c)
             buf[pp * KCH + c] =
@@ -860,9 +867,14 @@ struct MatEngine {
     u32x4 kb[2][NLD], vb[2][NLD];
     load_pages(0, k_voff, 64, kb[0]);
     load_pages(0, v_voff, 1024, vb[0]);
+    // the K stream tells the page-id registers when it enters a new page
+    auto k_entered = [&](int tile) {
+      const int q = off0 + tile * PPT;
+      if ((q & sub_mask) == 0) ids.k_stream_at(q >> sh);
+    };
     if (n_tiles > 1) {
       load_pages(1, k_voff, 64, kb[1]);
-      ids.k_stream_at(PPT);
+      k_entered(1);
     }
 
     auto step = [&](int tile, u32x4* kbuf, u32x4* vbuf, u32x4* v_next) {
@@ -873,9 +885,11 @@ struct MatEngine {
         const char* kn = static_cast<const char*>(p.k_new) + (int64_t(b) * p.n_kv_heads + kvh) * ROW;
         const char* vn = static_cast<const char*>(p.v_new) + (int64_t(b) * p.n_kv_heads + kvh) * ROW;
         const int pos = L - 1;
-        const int page_rel = (pos >> 4) - page0;
-        const int pp_new = page_rel - tile * PPT;
-        char* pb = const_cast<char*>(kv_base) + int64_t(ids.get(page_rel)) * p.small_bytes;
+        const int r_new = (pos >> 4) - ((p_lo << sh) + blk0);     // block of the new token, relative to the chunk
+        const int pp_new = r_new - tile * PPT;
+        const int page_rel = (off0 + r_new) >> sh;
+        char* pb = const_cast<char*>(kv_base) + int64_t(ids.get(page_rel)) * p.small_bytes +
+                   ((off0 + r_new) & sub_mask) * (T * ROW);
         const bool store = ids.writable(page_rel);
         if (n == (pos & 15)) {
 #pragma unroll
@@ -896,7 +910,7 @@ struct MatEngine {
             mine = true;
           }
         }
-        if (mine && store) *reinterpret_cast<u32x4*>(pb + V_OFF + (pos & 15) * ROW + (lane % LPT) * 16) = v_app;
+        if (mine && store) *reinterpret_cast<u32x4*>(pb + p.v_offset + (pos & 15) * ROW + (lane % LPT) * 16) = v_app;
       }
 
       // scores: lane (n, j) gets head n, tokens 4j .. 4j+3 of each page
@@ -912,7 +926,7 @@ struct MatEngine {
 
       if (tile + 2 < n_tiles) {
         load_pages(tile + 2, k_voff, 64, kbuf);
-        ids.k_stream_at((tile + 2) * PPT);
+        k_entered(tile + 2);
       }
 
       const int tile_tok = tok0 + tile * PPT * T;
@@ -1239,13 +1253,11 @@ DecodeFn pick_g(bool mat, bool quad, int G) {
   constexpr int kRow = D * E::kBytes;
   if constexpr (E::kBytes == 2) {
     if (mat) {
-      if constexpr (kRow <= 256) {
-        switch (G) {
-          case 1: return decode_partial_kernel<MatEngine<D, 1>>;
-          case 2: return decode_partial_kernel<MatEngine<D, 2>>;
-          case 4: return decode_partial_kernel<MatEngine<D, 4>>;
-          default: break;
-        }
+      switch (G) {
+        case 1: return decode_partial_kernel<MatEngine<D, 1>>;
+        case 2: return decode_partial_kernel<MatEngine<D, 2>>;
+        case 4: return decode_partial_kernel<MatEngine<D, 4>>;
+        default: break;
       }
       if (G == 16) return decode_partial_kernel<MatEngine<D, 16>>;
       return decode_partial_kernel<MatEngine<D, 8>>;
@@ -1306,7 +1318,7 @@ struct Geometry {
   const jenga::Kind* kind;
   int G;
   bool quad;             // 16-token pages, vector-ALU engine
-  bool mat;              // 16-token pages, matrix-core engine
+  bool mat;              // bf16, pages of 16 tokens or more, matrix-core engine
   int tile_log2;
   int chunk_tiles;       // 0: automatic
   int min_chunk_tiles;
@@ -1327,16 +1339,18 @@ int decode_geometry(const jenga_pool* pool, int32_t kind, int32_t n_q_heads, int
   if (n_q_heads % k.desc.n_kv_heads != 0) return JENGA_ERR_INVALID;
   const int G = n_q_heads / k.desc.n_kv_heads;
   if (G != 1 && G != 2 && G != 4 && G != 8 && G != 16) return JENGA_ERR_UNSUPPORTED;
-  if (G == 16 && !(k.desc.dtype == JENGA_BF16 && k.t_log2 == 4)) return JENGA_ERR_UNSUPPORTED;
+  if (G == 16 && !(k.desc.dtype == JENGA_BF16 && k.t_log2 >= 4)) return JENGA_ERR_UNSUPPORTED;
   const int row = k.desc.head_dim * k.elem_bytes;
   const int T = k.desc.tokens_per_page;
   out->kind = &k;
   out->G = G;
-  // 16-token pages: bf16 K/V goes to the matrix-core engine, except 256-element rows with up to 4
-  // query heads per KV head, where the quad engine measures 0.7 % faster; fp32 K/V goes to the
-  // quad engine up to 4 heads per KV head.  Everything else takes the general engine.
-  out->mat = k.t_log2 == 4 && k.desc.dtype == JENGA_BF16 && (row <= 256 || G >= 8);
-  out->quad = k.t_log2 == 4 && G <= 4 && row <= 512;
+  // bf16 K/V in pages of 16 tokens or more goes to the matrix-core engine, except 16-token pages of
+  // 256-element rows with up to 4 query heads per KV head, where the quad engine measures 0.7 %
+  // faster; fp32 K/V in 16-token pages goes to the quad engine up to 4 heads per KV head.
+  // Everything else takes the general engine.
+  out->quad = k.t_log2 == 4 && G <= 4 && row <= 512 &&
+              (k.desc.dtype == JENGA_F32 || row == 512);
+  out->mat = k.t_log2 >= 4 && k.desc.dtype == JENGA_BF16 && !out->quad;
   const bool paged16 = out->mat || out->quad;      // tiles of 8 KiB K + 8 KiB V in whole pages
   const int tile_tokens = paged16 ? (8 / (row / 64)) * 16 : 8 * (kWave / (row / 16));
   out->tile_log2 = 0;
