@@ -1,0 +1,303 @@
+// Decode engine on the matrix cores: bf16 K/V, pages of 16 tokens or more (see kernels.hip for the front end).
+#pragma once
+
+#include "decode_common.hpp"
+
+namespace {
+
+// ---- engine for bf16 K/V in pages of 16 tokens or more: both contractions on the matrix cores
+//
+// The work per 16-token block is a small dense contraction, scores = K[16 x D] . Q^T[D x G] and
+// out += P[G x 16] . V[16 x D], and the matrix cores take it off the vector ALUs altogether:
+// with 8 heads on every K/V byte those can no longer keep up with HBM (the quad engine would
+// need about 70 vector instructions per KiB), and with fewer heads the loads still issue
+// earlier and more evenly when so little else competes for the issue slots.  The G heads are
+// padded to the 16 rows / columns of the instructions.  Operand layouts (lane l, n = l % 16,
+// j = l / 16), checked on the device: A holds row n and B holds column n, each with
+// consecutive k (8j .. 8j+7 for 16x16x32, 4j .. 4j+3 for 16x16x16); the result holds column n,
+// rows 4j .. 4j+3.
+//   scores  v_mfma_f32_16x16x32_bf16, A = K page (row = token, k = d): lane (n, j) reads the
+//           16 bytes at d = 8j of each 64-byte piece of token n's row -- a plain 16-byte load,
+//           64-byte runs per token as in the quad engine.  B = Q (column = head, zero for the
+//           padding heads).  Result: lane (n, j) holds head n, tokens 4j .. 4j+3 of the page.
+//   values  v_mfma_f32_16x16x16_bf16, A = P (row = head, k = token of the page): exactly the
+//           four probabilities lane (n, j) holds after the softmax.  B = V (k = token,
+//           column = d) wants four tokens of one column per lane, but V arrives row-major:
+//           the rows go through LDS and come back through ds_read_b64_tr_b16, which hands
+//           lane (n, j) column n of the 4 rows whose addresses lanes 4r .. 4r+3 of its 16-lane
+//           group supplied.  Result: lane (n, j) holds output element 16 * block + n of heads
+//           4j .. 4j+3.
+// The instruction takes bf16 operands; a probability goes in as the sum of two bf16 numbers
+// (its rounding and the rounding of the remainder, 16 significant bits together) in two
+// products, so the result stays within fp32 rounding of an fp32 weighted sum -- the matrix
+// cores are idle most of the time anyway.
+template <int D_, int G_>
+struct MatEngine {
+  using E = BF16;
+  static constexpr int D = D_, G = G_;
+  static constexpr int T = 16;                 // tokens per block; a page holds 1, 2, 4 or 8 blocks
+  static constexpr int ROW = D * 2;            // bytes per token row
+  static constexpr int KCH = ROW / 64;         // k-steps of the score product == 1 KiB loads per page
+  static constexpr int PPT = 8 / KCH;          // blocks per tile (1, 2 or 4)
+  static constexpr int NLD = 8;                // 16-byte loads per lane and tile, K and V alike
+  static constexpr int LPT = ROW / 16;         // V loads: lanes per token row
+  static constexpr int TPL = kWave / LPT;      // V loads: token rows per load
+  static constexpr int NBLK = D / 16;          // 16-wide blocks of the output row
+  static constexpr int LROW = ROW + 32;        // LDS row pitch: 8 banks further per row
+  static constexpr int kTileLog2 = PPT == 1 ? 4 : PPT == 2 ? 5 : 6;
+  static constexpr int kLdsFloats = PPT * T * LROW / 4;
+  static_assert(KCH == 2 || KCH == 4 || KCH == 8, "row size");
+  static_assert(G <= 16, "heads are padded to 16");
+
+  typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+  typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+  typedef short s16x4 __attribute__((ext_vector_type(4)));
+  typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+  // max / sum over the four lanes n, n + 16, n + 32, n + 48
+  __device__ __forceinline__ static float across_groups_max(float x) {
+    unsigned u = __float_as_uint(x);
+    auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    x = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+    u = __float_as_uint(x);
+    r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+  }
+  __device__ __forceinline__ static float across_groups_sum(float x) {
+    unsigned u = __float_as_uint(x);
+    auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    x = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+    u = __float_as_uint(x);
+    r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+  }
+
+  __device__ __forceinline__ static void run(const DecodeParams& p, int lane, int b, int kvh, int L, int tile0,
+                             int n_tiles, int append_tile, int64_t slot, float* lds) {
+    // Pages of 16, 32, 64 or 128 tokens are read as runs of 16-token blocks: block q (counted
+    // from the first visible page) lies in page q >> sh at row offset (q & sub_mask) * 16.
+    const int sh = p.t_log2 - 4;
+    const int sub_mask = (1 << sh) - 1;
+    int lo_tok, p_lo, p_hi;
+    visible_pages(L, p.window, p.t_log2, &lo_tok, &p_lo, &p_hi);
+    const int blk0 = tile0 * PPT;                              // first block of the chunk
+    const int page0 = p_lo + (blk0 >> sh);
+    const int off0 = blk0 & sub_mask;                          // its place inside page0
+    const int n_blk = min(n_tiles * PPT, ((p_hi - p_lo) << sh) - blk0);
+    const int n_pages = (off0 + n_blk + sub_mask) >> sh;
+    const int tok0 = ((p_lo << sh) + blk0) * T;
+    char* v_lds = reinterpret_cast<char*>(lds);
+
+    PageIds ids;
+    ids.init(p.block_table + int64_t(b) * p.bt_stride + page0, n_pages, lane, p.max_page_id);
+
+    const int n = lane & 15, j = lane >> 4;
+    const int v_row = lane / LPT;                                        // V loads: row v_row + TPL * c of the page
+    const char* kv_base = p.layer_base + int64_t(kvh) * p.head_stride;   // wave-uniform
+    const unsigned k_voff = n * ROW + j * 16;                            // A operand of the score product
+    const unsigned v_voff = p.v_offset + lane * 16;
+    const unsigned lds_wr = v_row * LROW + (lane % LPT) * 16;            // this lane's V bytes (+ row offset)
+    const unsigned lds_rd = (4 * j + (n >> 2)) * LROW + (n & 3) * 8;     // transposed read (+ page, + block)
+
+    // B operand of the score product: head n (zero rows for the padding heads)
+    bf16x8 qb[KCH];
+#pragma unroll
+    for (int c = 0; c < KCH; ++c) {
+      u32x4 w = u32x4{0, 0, 0, 0};
+      if (n < G)
+        w = *reinterpret_cast<const u32x4*>(static_cast<const char*>(p.q) +
+                                           (int64_t(b) * p.n_q_heads + kvh * G + n) * ROW + j * 16 + c * 64);
+      qb[c] = __builtin_bit_cast(bf16x8, w);
+    }
+
+    float m = kNegBig, l = 0.f;        // of head n; l is this lane's share (its tokens only)
+    f32x4 acc[NBLK];
+#pragma unroll
+    for (int blk = 0; blk < NBLK; ++blk) acc[blk] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    auto load_pages = [&](int tile, unsigned voff, int step, u32x4* buf) {
+#pragma unroll
+      for (int pp = 0; pp < PPT; ++pp) {
+        const int r = tile * PPT + pp;
+        if (PPT == 1 || r < n_blk) {
+          const int q = off0 + r;
+          const char* pb = kv_base + int64_t(ids.get(q >> sh)) * p.small_bytes + (q & sub_mask) * (T * ROW);
+#pragma unroll
+          for (int c = 0; c < KCH; ++c)
+            buf[pp * KCH + c] =
+                __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(pb + voff + c * step));
+        } else {
+#pragma unroll
+          for (int c = 0; c < KCH; ++c) buf[pp * KCH + c] = u32x4{0, 0, 0, 0};
+        }
+      }
+    };
+
+    // two tiles deep, as in the quad engine
+    u32x4 kb[2][NLD], vb[2][NLD];
+    load_pages(0, k_voff, 64, kb[0]);
+    load_pages(0, v_voff, 1024, vb[0]);
+    // the K stream tells the page-id registers when it enters a new page
+    auto k_entered = [&](int tile) {
+      const int q = off0 + tile * PPT;
+      if ((q & sub_mask) == 0) ids.k_stream_at(q >> sh);
+    };
+    if (n_tiles > 1) {
+      load_pages(1, k_voff, 64, kb[1]);
+      k_entered(1);
+    }
+
+    auto step = [&](int tile, u32x4* kbuf, u32x4* vbuf, u32x4* v_next) {
+      if (tile + 1 < n_tiles) load_pages(tile + 1, v_voff, 1024, v_next);
+
+      // fused append: rows of the token at L - 1 come from k_new / v_new and are stored into the page
+      if (tile == append_tile) {
+        const char* kn = static_cast<const char*>(p.k_new) + (int64_t(b) * p.n_kv_heads + kvh) * ROW;
+        const char* vn = static_cast<const char*>(p.v_new) + (int64_t(b) * p.n_kv_heads + kvh) * ROW;
+        const int pos = L - 1;
+        const int r_new = (pos >> 4) - ((p_lo << sh) + blk0);     // block of the new token, relative to the chunk
+        const int pp_new = r_new - tile * PPT;
+        const int page_rel = (off0 + r_new) >> sh;
+        char* pb = const_cast<char*>(kv_base) + int64_t(ids.get(page_rel)) * p.small_bytes +
+                   ((off0 + r_new) & sub_mask) * (T * ROW);
+        const bool store = ids.writable(page_rel);
+        if (n == (pos & 15)) {
+#pragma unroll
+          for (int c = 0; c < KCH; ++c) {
+            const u32x4 k_app = *reinterpret_cast<const u32x4*>(kn + j * 16 + c * 64);
+            if (store) *reinterpret_cast<u32x4*>(pb + k_voff + c * 64) = k_app;
+#pragma unroll
+            for (int pp = 0; pp < PPT; ++pp)
+              if (pp == pp_new) kbuf[pp * KCH + c] = k_app;
+          }
+        }
+        const u32x4 v_app = *reinterpret_cast<const u32x4*>(vn + (lane % LPT) * 16);
+        bool mine = false;
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+          if ((i / KCH) * T + (i % KCH) * TPL + v_row == pp_new * T + (pos & 15)) {
+            vbuf[i] = v_app;
+            mine = true;
+          }
+        }
+        if (mine && store) *reinterpret_cast<u32x4*>(pb + p.v_offset + (pos & 15) * ROW + (lane % LPT) * 16) = v_app;
+      }
+
+      // scores: lane (n, j) gets head n, tokens 4j .. 4j+3 of each page
+      f32x4 s[PPT];
+#pragma unroll
+      for (int pp = 0; pp < PPT; ++pp) {
+        s[pp] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int c = 0; c < KCH; ++c)
+          s[pp] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kbuf[pp * KCH + c]), qb[c],
+                                                          s[pp], 0, 0, 0);
+      }
+
+      if (tile + 2 < n_tiles) {
+        load_pages(tile + 2, k_voff, 64, kbuf);
+        k_entered(tile + 2);
+      }
+
+      const int tile_tok = tok0 + tile * PPT * T;
+      const bool clean = tile_tok >= lo_tok && tile_tok + PPT * T <= L;
+#pragma unroll
+      for (int pp = 0; pp < PPT; ++pp)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) s[pp][i] *= p.scale_log2;
+      if (!clean) {
+#pragma unroll
+        for (int pp = 0; pp < PPT; ++pp)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            const int t = tile_tok + pp * T + 4 * j + i;
+            if (t < lo_tok || t >= L) s[pp][i] = kNegBig;
+          }
+        // V rows outside the visible set may hold anything (even NaN): make them zero
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+          const int t = tile_tok + (i / KCH) * T + (i % KCH) * TPL + v_row;
+          if (t < lo_tok || t >= L) vbuf[i] = u32x4{0, 0, 0, 0};
+        }
+      }
+
+      // V rows into LDS, row-major
+#pragma unroll
+      for (int i = 0; i < NLD; ++i)
+        *reinterpret_cast<u32x4*>(v_lds + ((i / KCH) * T + (i % KCH) * TPL) * LROW + lds_wr) = vbuf[i];
+
+      // online softmax of head n
+      float mx = s[0][0];
+#pragma unroll
+      for (int pp = 0; pp < PPT; ++pp)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) mx = fmaxf(mx, s[pp][i]);
+      const float m_new = fmaxf(m, across_groups_max(mx));
+      const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+      bf16x4 prob_hi[PPT], prob_lo[PPT];
+      float sum = 0.f;
+#pragma unroll
+      for (int pp = 0; pp < PPT; ++pp)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          float e = __builtin_amdgcn_exp2f(s[pp][i] - m_new);
+          if (!clean) e = (s[pp][i] == kNegBig) ? 0.f : e;
+          const __bf16 hi = static_cast<__bf16>(e);
+          prob_hi[pp][i] = hi;
+          prob_lo[pp][i] = static_cast<__bf16>(e - static_cast<float>(hi));
+          sum += e;
+        }
+      l = fmaf(l, alpha, sum);
+      m = m_new;
+
+      // The accumulator rows of this lane belong to heads 4j .. 4j+3: fetch their factors.  Once
+      // the running maxima have settled every factor is exactly 1 and the step is skipped.
+      if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
+        float a[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          a[i] = __int_as_float(__builtin_amdgcn_ds_bpermute(4 * (4 * j + i), __float_as_int(alpha)));
+#pragma unroll
+        for (int blk = 0; blk < NBLK; ++blk)
+#pragma unroll
+          for (int i = 0; i < 4; ++i) acc[blk][i] *= a[i];
+      }
+
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
+#pragma unroll
+      for (int pp = 0; pp < PPT; ++pp)
+#pragma unroll
+        for (int blk = 0; blk < NBLK; ++blk) {
+          const s16x4 v4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (lds_s16x4_ptr)(v_lds + pp * T * LROW + lds_rd + blk * 32));
+          const bf16x4 vt = __builtin_bit_cast(bf16x4, v4);
+          acc[blk] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(prob_hi[pp], vt, acc[blk], 0, 0, 0);
+          acc[blk] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(prob_lo[pp], vt, acc[blk], 0, 0, 0);
+        }
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+    };
+
+    for (int tile = 0; tile < n_tiles; tile += 2) {
+      step(tile, kb[0], vb[0], vb[1]);
+      if (tile + 1 < n_tiles) step(tile + 1, kb[1], vb[1], vb[0]);
+    }
+
+    l = across_groups_sum(l);
+    // one partial record: lane (n, j) holds element 16 * blk + n of heads 4j .. 4j+3
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int h = 4 * j + i;
+      if (h < G) {
+        float* dst = p.ws_acc + (slot * G + h) * D + n;
+#pragma unroll
+        for (int blk = 0; blk < NBLK; ++blk) dst[blk * 16] = acc[blk][i];
+      }
+    }
+    if (j == 0 && n < G) *reinterpret_cast<float2*>(p.ws_ml + (slot * G + n) * 2) = make_float2(m, l);
+  }
+};
+
+}  // namespace

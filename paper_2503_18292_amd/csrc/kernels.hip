@@ -45,990 +45,12 @@
 #include <unordered_map>
 
 #include "pool_internal.hpp"
+#include "decode_common.hpp"
+#include "engine_mat.hpp"
+#include "engine_quad.hpp"
+#include "engine_row.hpp"
 
 namespace {
-
-constexpr int kWave = 64;
-constexpr int kMaxBatch = 1024;         // per-request prefix sums are kept in LDS
-constexpr int kMaxPartitions = 8192;    // bound of the automatic grid (sizes the workspace)
-// Starting on a segment (block-table row, query rows, first loads, final merge and store) costs a
-// wavefront about as long as streaming two tiles (measured: 4.4 to 5 us against 2.5 us per
-// tile); the flat space charges every segment a few units before its first tile, so that a
-// chunk that spans a segment boundary gets fewer tiles and finishes with the others.  Measured
-// with 1, 2, 3, 4 and 6 units on four workloads: 3 is best or equal to the best on each.
-constexpr int kSegStartUnits = 3;
-constexpr float kNegBig = -1.0e30f;     // finite stand-in for -inf: keeps exp2(m - m) well defined
-
-struct DecodeParams {
-  const char* layer_base;     // pool base + layer * slice_bytes
-  int64_t small_bytes;        // page stride
-  int32_t head_stride;        // bytes between KV heads inside a layer slice: 2 * T * D * e
-  int32_t v_offset;           // bytes from a head's K rows to its V rows: T * D * e
-  int32_t t_log2;
-  int32_t n_kv_heads;
-  int32_t n_q_heads;
-  int32_t max_page_id;        // ids read from the block table are clamped to [0, max_page_id]
-  const void* q;
-  const int32_t* block_table;
-  int32_t bt_stride;
-  const int32_t* seq_lens;
-  int32_t batch;
-  int32_t max_seq_len;
-  int32_t window;
-  float scale_log2;           // softmax scale * log2(e): scores live in the base-2 domain
-  int32_t chunk_tiles;        // > 0: tiles per partition; 0: ceil(W / gridDim.x)
-  int32_t min_chunk_tiles;    // lower bound of the automatic chunk
-  const void* k_new;          // fused append: [batch][n_kv_heads][D] rows of the token at L - 1, or NULL
-  const void* v_new;
-  float* ws_acc;              // [slot][G][D]
-  float* ws_ml;               // [slot][G][2]  (running max, running sum)
-};
-
-// Visible pages [p_lo, p_hi) and first visible token of a request of length L.
-__device__ __forceinline__ void visible_pages(int L, int window, int t_log2, int* lo_tok,
-                                              int* p_lo, int* p_hi) {
-  const int lo = window > 0 ? max(0, L - window) : 0;
-  *lo_tok = lo;
-  *p_lo = lo >> t_log2;
-  *p_hi = (L + (1 << t_log2) - 1) >> t_log2;
-}
-
-// Units of the flat space one (request, KV head) segment takes: kSegStartUnits, then one per
-// tile (of 2^tile_log2 tokens, counted from the first visible page).  0 for an empty request.
-__device__ __forceinline__ int units_of(int L, int window, int t_log2, int tile_log2) {
-  if (L <= 0) return 0;
-  int lo_tok, p_lo, p_hi;
-  visible_pages(L, window, t_log2, &lo_tok, &p_lo, &p_hi);
-  return kSegStartUnits + ((((p_hi - p_lo) << t_log2) + (1 << tile_log2) - 1) >> tile_log2);
-}
-
-// Inclusive prefix sums of units * n_kv_heads per request into LDS, lengths next to them.
-// Returns W.  All 64 lanes of the (single-wave) block take part.
-__device__ __forceinline__ int scan_requests(const int32_t* seq_lens, int batch, int max_seq_len,
-                                             int window, int t_log2, int tile_log2, int n_kv_heads,
-                                             int lane, int* s_incl, int* s_len) {
-  int run = 0;
-  for (int c0 = 0; c0 < batch; c0 += kWave) {
-    const int i = c0 + lane;
-    const int Li = i < batch ? min(seq_lens[i], max_seq_len) : 0;
-    int incl = units_of(Li, window, t_log2, tile_log2) * n_kv_heads;
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) {
-      const int up = __shfl_up(incl, off);
-      if (lane >= off) incl += up;
-    }
-    if (i < batch) {
-      s_incl[i] = run + incl;
-      s_len[i] = Li;
-    }
-    run += __builtin_amdgcn_readlane(incl, kWave - 1);
-  }
-  __syncthreads();
-  return run;
-}
-
-__device__ __forceinline__ int chunk_of(int chunk_tiles, int min_chunk_tiles, int W, int n_part) {
-  return chunk_tiles > 0 ? chunk_tiles : max(min_chunk_tiles, (W + n_part - 1) / n_part);
-}
-
-// First request whose inclusive prefix exceeds flat position x (x < W).
-__device__ __forceinline__ int find_request(const int* s_incl, int batch, int x, int lane) {
-  for (int c0 = 0; c0 < batch; c0 += kWave) {
-    const int i = c0 + lane;
-    const bool past = i < batch && s_incl[i] > x;
-    const unsigned long long hit = __ballot(past);
-    if (hit) return c0 + __builtin_ctzll(hit);
-  }
-  return batch - 1;
-}
-
-// ---- cross-lane helpers ------------------------------------------------------------
-template <int CTRL>
-__device__ __forceinline__ float dpp_add(float x) {
-  const int y = __builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true);
-  return x + __int_as_float(y);
-}
-
-template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ float dpp_max(float x) {
-  const int y = __builtin_amdgcn_update_dpp(__float_as_int(x), __float_as_int(x), CTRL, ROW_MASK, 0xf, false);
-  return fmaxf(x, __int_as_float(y));
-}
-
-// Maximum over the wave, in an SGPR-uniform value.
-__device__ __forceinline__ float wave_max(float x) {
-  x = dpp_max<0xB1, 0xf>(x);    // lane ^ 1
-  x = dpp_max<0x4E, 0xf>(x);    // lane ^ 2
-  x = dpp_max<0x124, 0xf>(x);   // row_ror:4
-  x = dpp_max<0x128, 0xf>(x);   // row_ror:8  -> every lane holds its row's maximum
-  x = dpp_max<0x142, 0xa>(x);   // row_bcast:15 into rows 1 and 3
-  x = dpp_max<0x143, 0xc>(x);   // row_bcast:31 into rows 2 and 3 -> lane 63 holds the maximum
-  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), kWave - 1));
-}
-
-// Sum over aligned groups of LANES lanes, result in every lane of the group.
-template <int LANES>
-__device__ __forceinline__ float group_sum(float x) {
-  static_assert(LANES == 8 || LANES == 16 || LANES == 32 || LANES == 64, "group size");
-  x = dpp_add<0xB1>(x);    // quad_perm [1,0,3,2]: lane ^ 1
-  x = dpp_add<0x4E>(x);    // quad_perm [2,3,0,1]: lane ^ 2
-  x = dpp_add<0x141>(x);   // row_half_mirror: the other quad of each 8 lanes
-  if constexpr (LANES >= 16) x = dpp_add<0x140>(x);   // row_mirror: the other half of each 16 lanes
-  if constexpr (LANES >= 32) {
-    // v_permlane16_swap exchanges odd rows of the first operand with even rows of the second;
-    // fed the same value twice, the two results hold each row and its neighbour row.
-    const unsigned u = __float_as_uint(x);
-    const auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
-    x = __uint_as_float(r[0]) + __uint_as_float(r[1]);
-  }
-  if constexpr (LANES >= 64) {
-    const unsigned u = __float_as_uint(x);
-    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-    x = __uint_as_float(r[0]) + __uint_as_float(r[1]);
-  }
-  return x;
-}
-
-// ---- element types ---------------------------------------------------------------
-struct F32 {
-  static constexpr int kBytes = 4;
-};
-struct BF16 {
-  static constexpr int kBytes = 2;
-};
-
-typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-typedef unsigned u32x4 __attribute__((ext_vector_type(4)));   // 16 bytes; a native vector, so it can be loaded non-temporally
-
-// <k, q> over the 16 bytes a lane holds.
-template <typename E>
-__device__ __forceinline__ float dot16(const u32x4& k, const u32x4& q) {
-  if constexpr (E::kBytes == 4) {
-    float s = __uint_as_float(k.x) * __uint_as_float(q.x);
-    s = fmaf(__uint_as_float(k.y), __uint_as_float(q.y), s);
-    s = fmaf(__uint_as_float(k.z), __uint_as_float(q.z), s);
-    s = fmaf(__uint_as_float(k.w), __uint_as_float(q.w), s);
-    return s;
-  } else {
-    // v_dot2_f32_bf16: two bf16 products accumulated in fp32 per instruction.  The words are
-    // copied to scalars first: a bit cast applied directly to a vector element read the
-    // first element every time with this compiler.
-    const unsigned kw[4] = {k.x, k.y, k.z, k.w};
-    const unsigned qw[4] = {q.x, q.y, q.z, q.w};
-    float s = 0.f;
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, kw[i]),
-                                          __builtin_bit_cast(bf16x2_t, qw[i]), s, false);
-    return s;
-  }
-}
-
-// The 16 bytes of a lane as fp32 values (4 for fp32 storage, 8 for bf16).
-template <typename E>
-__device__ __forceinline__ void unpack16(const u32x4& v, float* f) {
-  if constexpr (E::kBytes == 4) {
-    f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y);
-    f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
-  } else {
-    f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xffff0000u);
-    f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xffff0000u);
-    f[4] = __uint_as_float(v.z << 16); f[5] = __uint_as_float(v.z & 0xffff0000u);
-    f[6] = __uint_as_float(v.w << 16); f[7] = __uint_as_float(v.w & 0xffff0000u);
-  }
-}
-
-// Page ids of the pages a wavefront is about to read, 128 at a time in two registers: lane j
-// of register (c & 1) holds the id of page 64*c + j (relative to the first page).  A
-// v_readlane turns one into a scalar, which makes the page's base address scalar too.  The
-// K stream runs one tile ahead of the V stream, so when K enters chunk c the register of
-// chunk c+1 (== that of chunk c-1, which V has just left) is reloaded.
-struct PageIds {
-  const int32_t* row;   // block-table entry of relative page 0
-  int n_pages;
-  int lane;
-  int max_id;
-  int reg0, reg1;       // two scalars, not an array: an indexed member would live in scratch memory
-
-  // A table entry that is negative or past the pool (a caller error: pages of the visible
-  // range must be resident) is clamped, so the kernel reads wrong data rather than faulting.
-  __device__ __forceinline__ int fetch(int first) const {
-    const int i = first + lane;
-    return i < n_pages ? min(max(row[i], 0), max_id) : 0;
-  }
-  __device__ __forceinline__ void init(const int32_t* r, int n, int l, int max_page_id) {
-    row = r; n_pages = n; lane = l; max_id = max_page_id;
-    reg0 = fetch(0);
-    reg1 = fetch(kWave);
-  }
-  // true when the table entry itself is a page of the pool (used before writing into it)
-  __device__ __forceinline__ bool writable(int page_rel) const {
-    const int raw = row[page_rel];
-    return raw >= 0 && raw <= max_id;
-  }
-  __device__ __forceinline__ int get(int page_rel) const {
-    const int r = (page_rel & kWave) ? reg1 : reg0;
-    return __builtin_amdgcn_readlane(r, page_rel & (kWave - 1));
-  }
-  // Call after the K stream has issued the loads of a tile starting at page_rel.
-  __device__ __forceinline__ void k_stream_at(int page_rel) {
-    if ((page_rel & (kWave - 1)) == 0 && page_rel > 0) {
-      const int next = fetch(page_rel + kWave);
-      if (page_rel & kWave) reg0 = next;
-      else reg1 = next;
-    }
-  }
-};
-
-// Writes one partial record.  acc lives in the V lane geometry: lanes [0, LPT) hold EPL
-// consecutive output elements each.
-template <int D, int G, int EPL>
-__device__ __forceinline__ void store_partial(const DecodeParams& p, int64_t slot, int lane, int lpt,
-                                              const float (&m)[G], const float (&l)[G],
-                                              const float (&acc)[G][EPL]) {
-  if (lane < lpt) {
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-      float* dst = p.ws_acc + (slot * G + g) * D + lane * EPL;
-#pragma unroll
-      for (int j = 0; j < EPL; j += 4)
-        *reinterpret_cast<float4*>(dst + j) =
-            make_float4(acc[g][j], acc[g][j + 1], acc[g][j + 2], acc[g][j + 3]);
-      if (lane == 0) *reinterpret_cast<float2*>(p.ws_ml + (slot * G + g) * 2) = make_float2(m[g], l[g]);
-    }
-  }
-}
-
-// ---- engine for 16-token pages: one token per quad of lanes -----------------------------
-//
-// The two operands are read in two different lane geometries:
-//   K  lane l reads token l/4 of the page: the (l%4)-th 16 bytes of every 64-byte piece of
-//      that token's row (a quad of lanes reads 64 contiguous bytes).  A lane therefore sums
-//      a quarter of ONE token's dot product in its own registers and the only cross-lane
-//      work per score is a sum over 4 lanes.
-//   V  lane l reads the 16 bytes at l*16 of every KiB of the page, i.e. it owns EPL output
-//      elements and sees token (l / LPT) of each load.
-// The softmax weights are produced in the K geometry (one token per quad) and consumed in
-// the V geometry, so they cross lanes through a small LDS array (broadcast reads, no bank
-// conflicts).  The running maximum is wave-uniform, which makes the final merge of the V
-// lane groups a plain sum.
-template <typename E_, int D_, int G_>
-struct QuadEngine {
-  using E = E_;
-  static constexpr int D = D_, G = G_;
-  static constexpr int T = 16;
-  static constexpr int ROW = D * E::kBytes;            // bytes per token row (<= 512 here)
-  static constexpr int EPL = 16 / E::kBytes;           // elements per 16 bytes
-  static constexpr int KCH = ROW / 64;                 // 64-byte pieces per row == 1 KiB loads per page
-  static constexpr int PPT = 8 / KCH;                  // pages per tile (1, 2 or 4)
-  static constexpr int NLD = 8;                        // loads per tile, K and V alike
-  static constexpr int LPT = ROW / 16;                 // V geometry: lanes per token row
-  static constexpr int TPL = kWave / LPT;              // V geometry: tokens per load
-  static constexpr int V_OFF = T * ROW;                // K rows come first in a (page, head) block
-  static constexpr int kTileLog2 = PPT == 1 ? 4 : PPT == 2 ? 5 : 6;
-  static constexpr int kLdsFloats = 2 * PPT * T * G;   // softmax weights of a tile, double buffered
-  // Pipeline depth, see run().  Measured: with 4 query heads per KV head the deeper pipeline is
-  // worth +6 % although some of its registers spill to accumulation registers; with 2 heads
-  // both depths run at the same speed.
-  static constexpr int kAhead = 1;
-  static_assert(KCH >= 2 && KCH <= 8, "row size");
-
-  __device__ __forceinline__ static void run(const DecodeParams& p, int lane, int b, int kvh, int L, int tile0,
-                             int n_tiles, int append_tile, int64_t slot, float* lds) {
-    int lo_tok, p_lo, p_hi;
-    visible_pages(L, p.window, 4, &lo_tok, &p_lo, &p_hi);
-    const int page0 = p_lo + tile0 * PPT;
-    const int n_pages = min(n_tiles * PPT, p_hi - page0);
-    const int tok0 = page0 * T;
-    float (*s_prob)[PPT * T][G] = reinterpret_cast<float (*)[PPT * T][G]>(lds);
-
-    PageIds ids;
-    ids.init(p.block_table + int64_t(b) * p.bt_stride + page0, n_pages, lane, p.max_page_id);
-
-    const char* kv_base = p.layer_base + int64_t(kvh) * p.head_stride;   // wave-uniform
-    const unsigned k_voff = (lane >> 2) * ROW + (lane & 3) * 16;         // K geometry
-    const unsigned v_voff = V_OFF + lane * 16;                           // V geometry
-    const int k_tok = lane >> 2;
-    const int v_grp = lane / LPT;
-
-    // query rows in the K geometry: for every 64-byte piece, this lane's 16 bytes
-    u32x4 qv[G][KCH];
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-      const char* qp = static_cast<const char*>(p.q) +
-                       (int64_t(b) * p.n_q_heads + kvh * G + g) * ROW + (lane & 3) * 16;
-#pragma unroll
-      for (int c = 0; c < KCH; ++c) qv[g][c] = *reinterpret_cast<const u32x4*>(qp + c * 64);
-    }
-
-    float m[G], l[G], acc[G][EPL];
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-      m[g] = kNegBig;
-      l[g] = 0.f;
-#pragma unroll
-      for (int j = 0; j < EPL; ++j) acc[g][j] = 0.f;
-    }
-
-    auto load_pages = [&](int tile, unsigned voff, int step, u32x4* buf) {
-#pragma unroll
-      for (int pp = 0; pp < PPT; ++pp) {
-        const int page_rel = tile * PPT + pp;
-        if (PPT == 1 || page_rel < n_pages) {
-          const char* pb = kv_base + int64_t(ids.get(page_rel)) * p.small_bytes;
-#pragma unroll
-          for (int c = 0; c < KCH; ++c)
-            buf[pp * KCH + c] =
-                __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(pb + voff + c * step));
-        } else {
-#pragma unroll
-          for (int c = 0; c < KCH; ++c) buf[pp * KCH + c] = u32x4{0, 0, 0, 0};
-        }
-      }
-    };
-
-    // Software pipeline.  AHEAD = 1 (two tiles deep): while tile t is computed, K(t+1), V(t+1)
-    // and (after the scores) K(t+2) are in flight, 16 to 32 KiB per wavefront.  AHEAD = 0: V(t)
-    // is issued at the start of tile t and K(t+1) after the scores, 8 to 16 KiB in flight (kept
-    // for comparison; not the configuration that is built).
-    // Loads return in order, so waiting for the oldest tile leaves the younger ones outstanding.
-    constexpr int AHEAD = kAhead;
-    u32x4 kb[1 + AHEAD][NLD], vb[1 + AHEAD][NLD];
-    load_pages(0, k_voff, 64, kb[0]);
-    if (AHEAD) {
-      load_pages(0, v_voff, 1024, vb[0]);
-      if (n_tiles > 1) {
-        load_pages(1, k_voff, 64, kb[AHEAD]);
-        ids.k_stream_at(PPT);
-      }
-    }
-
-    auto step = [&](int tile, u32x4* kbuf, u32x4* vbuf, u32x4* v_next) {
-      if (tile + AHEAD < n_tiles) load_pages(tile + AHEAD, v_voff, 1024, v_next);
-
-      // Fused append: the wavefront whose chunk holds the tile of the newest token (position
-      // L - 1) takes that token's rows from k_new / v_new instead of the pool and stores them
-      // into the page.  The rows are fetched here, once per (request, head), rather than held
-      // in registers through the whole loop.
-      if (tile == append_tile) {
-        const char* kn = static_cast<const char*>(p.k_new) + (int64_t(b) * p.n_kv_heads + kvh) * ROW;
-        const char* vn = static_cast<const char*>(p.v_new) + (int64_t(b) * p.n_kv_heads + kvh) * ROW;
-        u32x4 k_app[KCH];
-#pragma unroll
-        for (int c = 0; c < KCH; ++c)
-          k_app[c] = *reinterpret_cast<const u32x4*>(kn + c * 64 + (lane & 3) * 16);
-        const u32x4 v_app = *reinterpret_cast<const u32x4*>(vn + (lane % LPT) * 16);
-        const int pos = L - 1;
-        const int page_rel = (pos >> 4) - page0;
-        const int pp_new = page_rel - tile * PPT;           // page of the tile that holds the new token
-        const int t_new = pp_new * T + (pos & 15);          // its index inside the tile
-        char* pb = const_cast<char*>(kv_base) + int64_t(ids.get(page_rel)) * p.small_bytes;
-        const bool store = ids.writable(page_rel);
-        if (k_tok == (pos & 15)) {
-#pragma unroll
-          for (int c = 0; c < KCH; ++c) {
-            if (store) *reinterpret_cast<u32x4*>(pb + k_voff + c * 64) = k_app[c];
-#pragma unroll
-            for (int pp = 0; pp < PPT; ++pp)
-              if (pp == pp_new) kbuf[pp * KCH + c] = k_app[c];
-          }
-        }
-        bool mine = false;
-#pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-          if ((i / KCH) * T + (i % KCH) * TPL + v_grp == t_new) {
-            vbuf[i] = v_app;
-            mine = true;
-          }
-        }
-        if (mine && store) *reinterpret_cast<u32x4*>(pb + V_OFF + (pos & 15) * ROW + (lane % LPT) * 16) = v_app;
-      }
-
-      // one score per (page of the tile, query head) and lane: token k_tok of that page
-      float s[PPT][G];
-#pragma unroll
-      for (int pp = 0; pp < PPT; ++pp)
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-          float x = 0.f;
-#pragma unroll
-          for (int c = 0; c < KCH; ++c) x += dot16<E>(kbuf[pp * KCH + c], qv[g][c]);
-          x = dpp_add<0xB1>(x);      // lane ^ 1
-          x = dpp_add<0x4E>(x);      // lane ^ 2: all four lanes of the quad hold the token's score
-          s[pp][g] = x * p.scale_log2;
-        }
-
-      if (tile + 1 + AHEAD < n_tiles) {
-        load_pages(tile + 1 + AHEAD, k_voff, 64, kbuf);
-        ids.k_stream_at((tile + 1 + AHEAD) * PPT);
-      }
-
-      const int tile_tok = tok0 + tile * PPT * T;           // first token of the tile
-      const bool clean = tile_tok >= lo_tok && tile_tok + PPT * T <= L;
-      if (!clean) {
-#pragma unroll
-        for (int pp = 0; pp < PPT; ++pp) {
-          const int t = tile_tok + pp * T + k_tok;
-          if (t < lo_tok || t >= L) {
-#pragma unroll
-            for (int g = 0; g < G; ++g) s[pp][g] = kNegBig;
-          }
-        }
-        // V rows outside the visible set may hold anything (even NaN): make them zero
-#pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-          const int t = tile_tok + (i / KCH) * T + (i % KCH) * TPL + v_grp;
-          if (t < lo_tok || t >= L) vbuf[i] = u32x4{0, 0, 0, 0};
-        }
-      }
-
-      float (*prob)[G] = s_prob[tile & 1];
-#pragma unroll
-      for (int g = 0; g < G; ++g) {
-        float mx = s[0][g];
-#pragma unroll
-        for (int pp = 1; pp < PPT; ++pp) mx = fmaxf(mx, s[pp][g]);
-        const float m_new = fmaxf(m[g], wave_max(mx));
-        const float alpha = __builtin_amdgcn_exp2f(m[g] - m_new);
-        float sum = 0.f;
-#pragma unroll
-        for (int pp = 0; pp < PPT; ++pp) {
-          float e = __builtin_amdgcn_exp2f(s[pp][g] - m_new);
-          if (!clean) e = (s[pp][g] == kNegBig) ? 0.f : e;
-          sum += e;
-          if ((lane & 3) == 0) prob[pp * T + k_tok][g] = e;
-        }
-        l[g] = fmaf(l[g], alpha, sum);
-        m[g] = m_new;
-#pragma unroll
-        for (int j = 0; j < EPL; ++j) acc[g][j] *= alpha;
-      }
-      __builtin_amdgcn_wave_barrier();
-
-#pragma unroll
-      for (int i = 0; i < NLD; ++i) {
-        const int t_in_tile = (i / KCH) * T + (i % KCH) * TPL + v_grp;
-        float w[G];
-#pragma unroll
-        for (int g = 0; g < G; ++g) w[g] = prob[t_in_tile][g];
-        float vf[EPL];
-        unpack16<E>(vbuf[i], vf);
-#pragma unroll
-        for (int g = 0; g < G; ++g)
-#pragma unroll
-          for (int j = 0; j < EPL; ++j) acc[g][j] = fmaf(w[g], vf[j], acc[g][j]);
-      }
-      __builtin_amdgcn_wave_barrier();
-    };
-
-    if (AHEAD) {
-      for (int tile = 0; tile < n_tiles; tile += 2) {
-        step(tile, kb[0], vb[0], vb[AHEAD]);
-        if (tile + 1 < n_tiles) step(tile + 1, kb[AHEAD], vb[AHEAD], vb[0]);
-      }
-    } else {
-      for (int tile = 0; tile < n_tiles; ++tile) step(tile, kb[0], vb[0], vb[0]);
-    }
-
-    // every quad of lanes carried the same l; the V lane groups share m, so they just add up
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-      float lt = l[g];
-#pragma unroll
-      for (int off = 4; off < kWave; off <<= 1) lt += __shfl_xor(lt, off);
-      l[g] = lt;
-#pragma unroll
-      for (int off = LPT; off < kWave; off <<= 1)
-#pragma unroll
-        for (int j = 0; j < EPL; ++j) acc[g][j] += __shfl_xor(acc[g][j], off);
-    }
-    store_partial<D, G, EPL>(p, slot, lane, LPT, m, l, acc);
-  }
-};
-
-// ---- engine for any page size: rows spread over lanes -----------------------------------
-//
-// K and V are read alike: a token's row is LPT lanes x 16 bytes, one wave-wide load covers
-// TPL = 64 / LPT consecutive tokens (1 KiB, contiguous in the page).  Every partial dot
-// product is summed over LPT lanes, so this engine spends several times more vector-ALU
-// work per byte than the one above; it covers what the other two are not built for (8-token
-// pages; fp32 K/V in pages other than 16 tokens, with 8 query heads per KV head, or 1 KiB rows).  Each group of LPT lanes runs
-// its own online softmax over the tokens it sees; the groups are merged once at the end.
-template <typename E_, int D_, int G_>
-struct RowEngine {
-  using E = E_;
-  static constexpr int D = D_, G = G_;
-  static constexpr int ROW = D * E::kBytes;
-  static constexpr int EPL = 16 / E::kBytes;
-  static constexpr int LPT = ROW / 16;
-  static constexpr int TPL = kWave / LPT;
-  static constexpr int NL = 8;                 // loads per tile
-  static constexpr int TT = NL * TPL;          // tokens per tile: 8, 16, 32 or 64
-  static constexpr int kTileLog2 = TT == 8 ? 3 : TT == 16 ? 4 : TT == 32 ? 5 : 6;
-  static constexpr int kLdsFloats = 0;
-
-  __device__ __forceinline__ static void run(const DecodeParams& p, int lane, int b, int kvh, int L, int tile0,
-                             int n_tiles, int append_tile, int64_t slot, float*) {
-    int lo_tok, p_lo, p_hi;
-    visible_pages(L, p.window, p.t_log2, &lo_tok, &p_lo, &p_hi);
-    const int t_mask = (1 << p.t_log2) - 1;
-    // tiles are counted from the first visible page; a tile may be a fraction of a page
-    const int first_tok = tile0 * TT;                       // relative to page p_lo
-    const int page0 = p_lo + (first_tok >> p.t_log2);
-    const int tok_off0 = first_tok & t_mask;                // offset of the chunk inside page0
-    const int n_pages = min((tok_off0 + n_tiles * TT + t_mask) >> p.t_log2, p_hi - page0);
-    const int abs0 = (page0 << p.t_log2) + tok_off0;        // absolute index of the chunk's first token
-
-    PageIds ids;
-    ids.init(p.block_table + int64_t(b) * p.bt_stride + page0, n_pages, lane, p.max_page_id);
-
-    const int sub = lane % LPT;
-    const int grp = lane / LPT;
-    const char* head_base = p.layer_base + int64_t(kvh) * p.head_stride + lane * 16;
-
-    u32x4 qv[G];
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-      const char* qp = static_cast<const char*>(p.q) +
-                       (int64_t(b) * p.n_q_heads + kvh * G + g) * ROW + sub * 16;
-      qv[g] = *reinterpret_cast<const u32x4*>(qp);
-    }
-
-    float m[G], l[G], acc[G][EPL];
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-      m[g] = kNegBig;
-      l[g] = 0.f;
-#pragma unroll
-      for (int j = 0; j < EPL; ++j) acc[g][j] = 0.f;
-    }
-
-    auto load_tile = [&](int tile, int v_off, u32x4* buf) {
-#pragma unroll
-      for (int i = 0; i < NL; ++i) {
-        const int tokr = tok_off0 + tile * TT + i * TPL;     // relative to page0, wave-uniform
-        const int page_rel = tokr >> p.t_log2;
-        if (page_rel < n_pages) {
-          const char* src = head_base + int64_t(ids.get(page_rel)) * p.small_bytes + v_off +
-                            (tokr & t_mask) * ROW;
-          buf[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src));
-        } else {
-          buf[i] = u32x4{0, 0, 0, 0};
-        }
-      }
-    };
-
-    u32x4 kbuf[NL], vbuf[NL];
-    load_tile(0, 0, kbuf);
-
-    for (int tile = 0; tile < n_tiles; ++tile) {
-      load_tile(tile, p.v_offset, vbuf);
-
-      // fused append (see the quad engine): rows of the token at L - 1 come from k_new / v_new
-      if (tile == append_tile) {
-        const int64_t off = (int64_t(b) * p.n_kv_heads + kvh) * ROW + sub * 16;
-        const u32x4 k_app = *reinterpret_cast<const u32x4*>(static_cast<const char*>(p.k_new) + off);
-        const u32x4 v_app = *reinterpret_cast<const u32x4*>(static_cast<const char*>(p.v_new) + off);
-        const int pos = L - 1;
-        const int page_rel = (pos >> p.t_log2) - page0;
-        bool mine = false;
-#pragma unroll
-        for (int i = 0; i < NL; ++i) {
-          if (abs0 + tile * TT + i * TPL + grp == pos) {
-            kbuf[i] = k_app;
-            vbuf[i] = v_app;
-            mine = true;
-          }
-        }
-        char* dst = const_cast<char*>(head_base) + int64_t(ids.get(page_rel)) * p.small_bytes +
-                    (pos & t_mask) * ROW - grp * ROW;     // head_base carries lane * 16 = grp * ROW + sub * 16
-        if (mine && ids.writable(page_rel)) {
-          *reinterpret_cast<u32x4*>(dst) = k_app;
-          *reinterpret_cast<u32x4*>(dst + p.v_offset) = v_app;
-        }
-      }
-
-      float s[NL][G];
-#pragma unroll
-      for (int i = 0; i < NL; ++i)
-#pragma unroll
-        for (int g = 0; g < G; ++g)
-          s[i][g] = group_sum<LPT>(dot16<E>(kbuf[i], qv[g])) * p.scale_log2;
-
-      if (tile + 1 < n_tiles) {
-        load_tile(tile + 1, 0, kbuf);
-        const int tokr = tok_off0 + (tile + 1) * TT;
-        if ((tokr & t_mask) == 0) ids.k_stream_at(tokr >> p.t_log2);
-      }
-
-      const int t_abs0 = abs0 + tile * TT + grp;
-      const bool clean = (abs0 + tile * TT >= lo_tok) && (abs0 + (tile + 1) * TT <= L);
-      bool valid[NL];
-#pragma unroll
-      for (int i = 0; i < NL; ++i) valid[i] = true;
-      if (!clean) {
-#pragma unroll
-        for (int i = 0; i < NL; ++i) {
-          const int t = t_abs0 + i * TPL;
-          valid[i] = (t >= lo_tok) && (t < L);
-          if (!valid[i]) {
-            vbuf[i] = u32x4{0, 0, 0, 0};             // masked rows may hold anything, even NaN
-#pragma unroll
-            for (int g = 0; g < G; ++g) s[i][g] = kNegBig;
-          }
-        }
-      }
-
-      float pr[NL][G];
-#pragma unroll
-      for (int g = 0; g < G; ++g) {
-        float mx = s[0][g];
-#pragma unroll
-        for (int i = 1; i < NL; ++i) mx = fmaxf(mx, s[i][g]);
-        const float m_new = fmaxf(m[g], mx);
-        const float alpha = __builtin_amdgcn_exp2f(m[g] - m_new);
-        float sum = 0.f;
-#pragma unroll
-        for (int i = 0; i < NL; ++i) {
-          float e = __builtin_amdgcn_exp2f(s[i][g] - m_new);
-          if (!clean) e = valid[i] ? e : 0.f;
-          pr[i][g] = e;
-          sum += e;
-        }
-        l[g] = fmaf(l[g], alpha, sum);
-        m[g] = m_new;
-#pragma unroll
-        for (int j = 0; j < EPL; ++j) acc[g][j] *= alpha;
-      }
-
-#pragma unroll
-      for (int i = 0; i < NL; ++i) {
-        float vf[EPL];
-        unpack16<E>(vbuf[i], vf);
-#pragma unroll
-        for (int g = 0; g < G; ++g)
-#pragma unroll
-          for (int j = 0; j < EPL; ++j) acc[g][j] = fmaf(pr[i][g], vf[j], acc[g][j]);
-      }
-    }
-
-    // merge the TPL token groups (lanes that hold the same elements of different tokens)
-#pragma unroll
-    for (int off = LPT; off < kWave; off <<= 1) {
-#pragma unroll
-      for (int g = 0; g < G; ++g) {
-        const float m_o = __shfl_xor(m[g], off);
-        const float l_o = __shfl_xor(l[g], off);
-        const float m_new = fmaxf(m[g], m_o);
-        const float a = __builtin_amdgcn_exp2f(m[g] - m_new);
-        const float c = __builtin_amdgcn_exp2f(m_o - m_new);
-        l[g] = l[g] * a + l_o * c;
-        m[g] = m_new;
-#pragma unroll
-        for (int j = 0; j < EPL; ++j) {
-          const float acc_o = __shfl_xor(acc[g][j], off);
-          acc[g][j] = acc[g][j] * a + acc_o * c;
-        }
-      }
-    }
-    store_partial<D, G, EPL>(p, slot, lane, LPT, m, l, acc);
-  }
-};
-
-// ---- engine for bf16 K/V in pages of 16 tokens or more: both contractions on the matrix cores
-//
-// The work per 16-token block is a small dense contraction, scores = K[16 x D] . Q^T[D x G] and
-// out += P[G x 16] . V[16 x D], and the matrix cores take it off the vector ALUs altogether:
-// with 8 heads on every K/V byte those can no longer keep up with HBM (the quad engine would
-// need about 70 vector instructions per KiB), and with fewer heads the loads still issue
-// earlier and more evenly when so little else competes for the issue slots.  The G heads are
-// padded to the 16 rows / columns of the instructions.  Operand layouts (lane l, n = l % 16,
-// j = l / 16), checked on the device: A holds row n and B holds column n, each with
-// consecutive k (8j .. 8j+7 for 16x16x32, 4j .. 4j+3 for 16x16x16); the result holds column n,
-// rows 4j .. 4j+3.
-//   scores  v_mfma_f32_16x16x32_bf16, A = K page (row = token, k = d): lane (n, j) reads the
-//           16 bytes at d = 8j of each 64-byte piece of token n's row -- a plain 16-byte load,
-//           64-byte runs per token as in the quad engine.  B = Q (column = head, zero for the
-//           padding heads).  Result: lane (n, j) holds head n, tokens 4j .. 4j+3 of the page.
-//   values  v_mfma_f32_16x16x16_bf16, A = P (row = head, k = token of the page): exactly the
-//           four probabilities lane (n, j) holds after the softmax.  B = V (k = token,
-//           column = d) wants four tokens of one column per lane, but V arrives row-major:
-//           the rows go through LDS and come back through ds_read_b64_tr_b16, which hands
-//           lane (n, j) column n of the 4 rows whose addresses lanes 4r .. 4r+3 of its 16-lane
-//           group supplied.  Result: lane (n, j) holds output element 16 * block + n of heads
-//           4j .. 4j+3.
-// The instruction takes bf16 operands; a probability goes in as the sum of two bf16 numbers
-// (its rounding and the rounding of the remainder, 16 significant bits together) in two
-// products, so the result stays within fp32 rounding of an fp32 weighted sum -- the matrix
-// cores are idle most of the time anyway.
-template <int D_, int G_>
-struct MatEngine {
-  using E = BF16;
-  static constexpr int D = D_, G = G_;
-  static constexpr int T = 16;                 // tokens per block; a page holds 1, 2, 4 or 8 blocks
-  static constexpr int ROW = D * 2;            // bytes per token row
-  static constexpr int KCH = ROW / 64;         // k-steps of the score product == 1 KiB loads per page
-  static constexpr int PPT = 8 / KCH;          // blocks per tile (1, 2 or 4)
-  static constexpr int NLD = 8;                // 16-byte loads per lane and tile, K and V alike
-  static constexpr int LPT = ROW / 16;         // V loads: lanes per token row
-  static constexpr int TPL = kWave / LPT;      // V loads: token rows per load
-  static constexpr int NBLK = D / 16;          // 16-wide blocks of the output row
-  static constexpr int LROW = ROW + 32;        // LDS row pitch: 8 banks further per row
-  static constexpr int kTileLog2 = PPT == 1 ? 4 : PPT == 2 ? 5 : 6;
-  static constexpr int kLdsFloats = PPT * T * LROW / 4;
-  static_assert(KCH == 2 || KCH == 4 || KCH == 8, "row size");
-  static_assert(G <= 16, "heads are padded to 16");
-
-  typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-  typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-  typedef short s16x4 __attribute__((ext_vector_type(4)));
-  typedef float f32x4 __attribute__((ext_vector_type(4)));
-
-  // max / sum over the four lanes n, n + 16, n + 32, n + 48
-  __device__ __forceinline__ static float across_groups_max(float x) {
-    unsigned u = __float_as_uint(x);
-    auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
-    x = fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-    u = __float_as_uint(x);
-    r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-  }
-  __device__ __forceinline__ static float across_groups_sum(float x) {
-    unsigned u = __float_as_uint(x);
-    auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
-    x = __uint_as_float(r[0]) + __uint_as_float(r[1]);
-    u = __float_as_uint(x);
-    r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-  }
-
-  __device__ __forceinline__ static void run(const DecodeParams& p, int lane, int b, int kvh, int L, int tile0,
-                             int n_tiles, int append_tile, int64_t slot, float* lds) {
-    // Pages of 16, 32, 64 or 128 tokens are read as runs of 16-token blocks: block q (counted
-    // from the first visible page) lies in page q >> sh at row offset (q & sub_mask) * 16.
-    const int sh = p.t_log2 - 4;
-    const int sub_mask = (1 << sh) - 1;
-    int lo_tok, p_lo, p_hi;
-    visible_pages(L, p.window, p.t_log2, &lo_tok, &p_lo, &p_hi);
-    const int blk0 = tile0 * PPT;                              // first block of the chunk
-    const int page0 = p_lo + (blk0 >> sh);
-    const int off0 = blk0 & sub_mask;                          // its place inside page0
-    const int n_blk = min(n_tiles * PPT, ((p_hi - p_lo) << sh) - blk0);
-    const int n_pages = (off0 + n_blk + sub_mask) >> sh;
-    const int tok0 = ((p_lo << sh) + blk0) * T;
-    char* v_lds = reinterpret_cast<char*>(lds);
-
-    PageIds ids;
-    ids.init(p.block_table + int64_t(b) * p.bt_stride + page0, n_pages, lane, p.max_page_id);
-
-    const int n = lane & 15, j = lane >> 4;
-    const int v_row = lane / LPT;                                        // V loads: row v_row + TPL * c of the page
-    const char* kv_base = p.layer_base + int64_t(kvh) * p.head_stride;   // wave-uniform
-    const unsigned k_voff = n * ROW + j * 16;                            // A operand of the score product
-    const unsigned v_voff = p.v_offset + lane * 16;
-    const unsigned lds_wr = v_row * LROW + (lane % LPT) * 16;            // this lane's V bytes (+ row offset)
-    const unsigned lds_rd = (4 * j + (n >> 2)) * LROW + (n & 3) * 8;     // transposed read (+ page, + block)
-
-    // B operand of the score product: head n (zero rows for the padding heads)
-    bf16x8 qb[KCH];
-#pragma unroll
-    for (int c = 0; c < KCH; ++c) {
-      u32x4 w = u32x4{0, 0, 0, 0};
-      if (n < G)
-        w = *reinterpret_cast<const u32x4*>(static_cast<const char*>(p.q) +
-                                           (int64_t(b) * p.n_q_heads + kvh * G + n) * ROW + j * 16 + c * 64);
-      qb[c] = __builtin_bit_cast(bf16x8, w);
-    }
-
-    float m = kNegBig, l = 0.f;        // of head n; l is this lane's share (its tokens only)
-    f32x4 acc[NBLK];
-#pragma unroll
-    for (int blk = 0; blk < NBLK; ++blk) acc[blk] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    auto load_pages = [&](int tile, unsigned voff, int step, u32x4* buf) {
-#pragma unroll
-      for (int pp = 0; pp < PPT; ++pp) {
-        const int r = tile * PPT + pp;
-        if (PPT == 1 || r < n_blk) {
-          const int q = off0 + r;
-          const char* pb = kv_base + int64_t(ids.get(q >> sh)) * p.small_bytes + (q & sub_mask) * (T * ROW);
-#pragma unroll
-          for (int c = 0; c < KCH; ++c)
-            buf[pp * KCH + c] =
-                __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(pb + voff + c * step));
-        } else {
-#pragma unroll
-          for (int c = 0; c < KCH; ++c) buf[pp * KCH + c] = u32x4{0, 0, 0, 0};
-        }
-      }
-    };
-
-    // two tiles deep, as in the quad engine
-    u32x4 kb[2][NLD], vb[2][NLD];
-    load_pages(0, k_voff, 64, kb[0]);
-    load_pages(0, v_voff, 1024, vb[0]);
-    // the K stream tells the page-id registers when it enters a new page
-    auto k_entered = [&](int tile) {
-      const int q = off0 + tile * PPT;
-      if ((q & sub_mask) == 0) ids.k_stream_at(q >> sh);
-    };
-    if (n_tiles > 1) {
-      load_pages(1, k_voff, 64, kb[1]);
-      k_entered(1);
-    }
-
-    auto step = [&](int tile, u32x4* kbuf, u32x4* vbuf, u32x4* v_next) {
-      if (tile + 1 < n_tiles) load_pages(tile + 1, v_voff, 1024, v_next);
-
-      // fused append: rows of the token at L - 1 come from k_new / v_new and are stored into the page
-      if (tile == append_tile) {
-        const char* kn = static_cast<const char*>(p.k_new) + (int64_t(b) * p.n_kv_heads + kvh) * ROW;
-        const char* vn = static_cast<const char*>(p.v_new) + (int64_t(b) * p.n_kv_heads + kvh) * ROW;
-        const int pos = L - 1;
-        const int r_new = (pos >> 4) - ((p_lo << sh) + blk0);     // block of the new token, relative to the chunk
-        const int pp_new = r_new - tile * PPT;
-        const int page_rel = (off0 + r_new) >> sh;
-        char* pb = const_cast<char*>(kv_base) + int64_t(ids.get(page_rel)) * p.small_bytes +
-                   ((off0 + r_new) & sub_mask) * (T * ROW);
-        const bool store = ids.writable(page_rel);
-        if (n == (pos & 15)) {
-#pragma unroll
-          for (int c = 0; c < KCH; ++c) {
-            const u32x4 k_app = *reinterpret_cast<const u32x4*>(kn + j * 16 + c * 64);
-            if (store) *reinterpret_cast<u32x4*>(pb + k_voff + c * 64) = k_app;
-#pragma unroll
-            for (int pp = 0; pp < PPT; ++pp)
-              if (pp == pp_new) kbuf[pp * KCH + c] = k_app;
-          }
-        }
-        const u32x4 v_app = *reinterpret_cast<const u32x4*>(vn + (lane % LPT) * 16);
-        bool mine = false;
-#pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-          if ((i / KCH) * T + (i % KCH) * TPL + v_row == pp_new * T + (pos & 15)) {
-            vbuf[i] = v_app;
-            mine = true;
-          }
-        }
-        if (mine && store) *reinterpret_cast<u32x4*>(pb + p.v_offset + (pos & 15) * ROW + (lane % LPT) * 16) = v_app;
-      }
-
-      // scores: lane (n, j) gets head n, tokens 4j .. 4j+3 of each page
-      f32x4 s[PPT];
-#pragma unroll
-      for (int pp = 0; pp < PPT; ++pp) {
-        s[pp] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int c = 0; c < KCH; ++c)
-          s[pp] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kbuf[pp * KCH + c]), qb[c],
-                                                          s[pp], 0, 0, 0);
-      }
-
-      if (tile + 2 < n_tiles) {
-        load_pages(tile + 2, k_voff, 64, kbuf);
-        k_entered(tile + 2);
-      }
-
-      const int tile_tok = tok0 + tile * PPT * T;
-      const bool clean = tile_tok >= lo_tok && tile_tok + PPT * T <= L;
-#pragma unroll
-      for (int pp = 0; pp < PPT; ++pp)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) s[pp][i] *= p.scale_log2;
-      if (!clean) {
-#pragma unroll
-        for (int pp = 0; pp < PPT; ++pp)
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const int t = tile_tok + pp * T + 4 * j + i;
-            if (t < lo_tok || t >= L) s[pp][i] = kNegBig;
-          }
-        // V rows outside the visible set may hold anything (even NaN): make them zero
-#pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-          const int t = tile_tok + (i / KCH) * T + (i % KCH) * TPL + v_row;
-          if (t < lo_tok || t >= L) vbuf[i] = u32x4{0, 0, 0, 0};
-        }
-      }
-
-      // V rows into LDS, row-major
-#pragma unroll
-      for (int i = 0; i < NLD; ++i)
-        *reinterpret_cast<u32x4*>(v_lds + ((i / KCH) * T + (i % KCH) * TPL) * LROW + lds_wr) = vbuf[i];
-
-      // online softmax of head n
-      float mx = s[0][0];
-#pragma unroll
-      for (int pp = 0; pp < PPT; ++pp)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) mx = fmaxf(mx, s[pp][i]);
-      const float m_new = fmaxf(m, across_groups_max(mx));
-      const float alpha = __builtin_amdgcn_exp2f(m - m_new);
-      bf16x4 prob_hi[PPT], prob_lo[PPT];
-      float sum = 0.f;
-#pragma unroll
-      for (int pp = 0; pp < PPT; ++pp)
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          float e = __builtin_amdgcn_exp2f(s[pp][i] - m_new);
-          if (!clean) e = (s[pp][i] == kNegBig) ? 0.f : e;
-          const __bf16 hi = static_cast<__bf16>(e);
-          prob_hi[pp][i] = hi;
-          prob_lo[pp][i] = static_cast<__bf16>(e - static_cast<float>(hi));
-          sum += e;
-        }
-      l = fmaf(l, alpha, sum);
-      m = m_new;
-
-      // The accumulator rows of this lane belong to heads 4j .. 4j+3: fetch their factors.  Once
-      // the running maxima have settled every factor is exactly 1 and the step is skipped.
-      if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {
-        float a[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-          a[i] = __int_as_float(__builtin_amdgcn_ds_bpermute(4 * (4 * j + i), __float_as_int(alpha)));
-#pragma unroll
-        for (int blk = 0; blk < NBLK; ++blk)
-#pragma unroll
-          for (int i = 0; i < 4; ++i) acc[blk][i] *= a[i];
-      }
-
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-      typedef s16x4 __attribute__((address_space(3))) * lds_s16x4_ptr;
-#pragma unroll
-      for (int pp = 0; pp < PPT; ++pp)
-#pragma unroll
-        for (int blk = 0; blk < NBLK; ++blk) {
-          const s16x4 v4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (lds_s16x4_ptr)(v_lds + pp * T * LROW + lds_rd + blk * 32));
-          const bf16x4 vt = __builtin_bit_cast(bf16x4, v4);
-          acc[blk] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(prob_hi[pp], vt, acc[blk], 0, 0, 0);
-          acc[blk] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(prob_lo[pp], vt, acc[blk], 0, 0, 0);
-        }
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-      __builtin_amdgcn_wave_barrier();
-    };
-
-    for (int tile = 0; tile < n_tiles; tile += 2) {
-      step(tile, kb[0], vb[0], vb[1]);
-      if (tile + 1 < n_tiles) step(tile + 1, kb[1], vb[1], vb[0]);
-    }
-
-    l = across_groups_sum(l);
-    // one partial record: lane (n, j) holds element 16 * blk + n of heads 4j .. 4j+3
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int h = 4 * j + i;
-      if (h < G) {
-        float* dst = p.ws_acc + (slot * G + h) * D + n;
-#pragma unroll
-        for (int blk = 0; blk < NBLK; ++blk) dst[blk * 16] = acc[blk][i];
-      }
-    }
-    if (j == 0 && n < G) *reinterpret_cast<float2*>(p.ws_ml + (slot * G + n) * 2) = make_float2(m, l);
-  }
-};
 
 // One wavefront per partition of the flat tile space (see the head of the file).
 template <class Eng>
