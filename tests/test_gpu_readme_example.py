@@ -1,0 +1,38 @@
+"""The decode-step example of README.md runs as printed and its result is the oracle's."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_readme_example_runs_and_is_right():
+    import torch
+    from oracle.attn import decode_attention_one
+    from workloads import layout
+    from workloads.configs import FULL, KindCfg
+    text = open(os.path.join(ROOT, "README.md")).read()
+    code = re.search(r"```python\n(.*?)```", text, re.S).group(1)
+    code = code.replace("64 << 30", "4 << 30")           # a smaller pool is enough for two requests
+    env = {}
+    exec(compile(code, "README.md", "exec"), env)
+    torch.cuda.synchronize()
+    out, q, mem, table, lens = env["out"], env["q"], env["mem"], env["table"], env["lens"]
+    assert torch.isfinite(out[1]).all()
+    # request 1 (300 tokens): only its last row was written by the example; put known K/V in the
+    # other rows, run the same call again and compare with the oracle
+    kd = KindCfg("full", FULL, "bf16", 21, 16, 8, 256, 16)
+    L = int(lens[1])
+    K = (torch.randn(8, L, 256) * 0.5).bfloat16()
+    V = (torch.randn(8, L, 256) * 0.5).bfloat16()
+    K[:, -1], V[:, -1] = env["k_new"][1].cpu(), env["v_new"][1].cpu()
+    layout.scatter_request(mem, kd, 3, table[1].tolist(), K, V, L)
+    env["pool"].paged_decode(0, 3, q, env["table_d"], env["lens_d"], 5000, 0, 256 ** -0.5, env["ws"], out,
+                             k_new=env["k_new"], v_new=env["v_new"])
+    torch.cuda.synchronize()
+    want = decode_attention_one(q[1].cpu().double().numpy(), K.double().numpy(), V.double().numpy(), 256 ** -0.5, 0)
+    assert np.abs(out[1].cpu().double().numpy() - want).max() <= 2e-2
+    env["pool"].destroy()
