@@ -208,6 +208,32 @@ def test_edge_lengths(ctx):
         r.close()
 
 
+@pytest.mark.parametrize("dtype,D,G,T", [("bf16", 128, 4, 16), ("bf16", 256, 2, 16), ("f32", 64, 2, 16), ("bf16", 64, 8, 32),
+                                         ("f32", 128, 8, 16)])
+def test_peaked_softmax_large_scores(dtype, D, G, T):
+    """K/V of large magnitude: scores of several hundred, the softmax is close to one-hot and the
+    exponent range is only survivable through the running maximum."""
+    print(f"[case] peaked {dtype} D={D} G={G} T={T}", flush=True)
+    cfg = custom_cfg(dtype, D, 2 * G, 2, FULL, hi=500, T=T)
+    cfg.value_sigma = 150.0
+    r = _runner(cfg, 61)
+    prepare(r)
+    r.device_step()
+    torch.cuda.synchronize()
+    for k, layer in r.schedule:
+        kd = r.cfg.kinds[k]
+        q = r.inputs[(k, layer)][0].cpu().double().numpy()
+        got = r.out[(k, layer)].cpu().double().numpy()
+        for b in range(cfg.batch):
+            K, V = r.contiguous_kv(k, layer, b)
+            want = decode_attention_one(q[b], K.double().numpy(), V.double().numpy(), r.scale(k), 0)
+            assert np.isfinite(got[b]).all()
+            # outputs are of the magnitude of V here: relative tolerance only
+            rel = np.linalg.norm(got[b] - want) / np.linalg.norm(want)
+            assert rel <= (1e-5 if dtype == "f32" else TOL_BF16_REL), rel
+    r.close()
+
+
 def test_empty_batch_entries_give_zeros():
     cfg = custom_cfg("bf16", 128, 4, 2, FULL)
     r = _runner(cfg, 4, ctx=np.array([40, 9, 100]))
