@@ -285,7 +285,8 @@ int64_t jenga_decode_workspace_bytes(const jenga_pool* pool, int32_t kind, int32
  *                resident (>= 0); other entries are never read
  *   seq_lens     device int32 [batch], each <= max_seq_len (larger ones are clamped)
  *   max_seq_len  host upper bound of seq_lens; sizes the grid; bt_stride * T >= max_seq_len
- *   window       0: none.  Pass the kind's window for WINDOW kinds.
+ *   window       0: none.  WINDOW kinds: the kind's window (a smaller positive one is allowed,
+ *                0 or a larger one is INVALID: those pages are not resident).
  *   pages_per_split  0: automatic (balanced partitions); else the partition size in pages of K/V
  *   workspace    device, >= jenga_decode_workspace_bytes(...), 16-byte aligned, caller-owned;
  *                holds per-partition (max, sum, accumulator) between the two kernels

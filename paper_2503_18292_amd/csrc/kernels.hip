@@ -357,6 +357,9 @@ int decode_geometry(const jenga_pool* pool, int32_t kind, int32_t n_q_heads, int
   if (!attention_kind(k)) return JENGA_ERR_INVALID;
   if (batch < 0 || max_seq_len < 0 || window < 0 || n_q_heads < 1 || pages_per_split < 0)
     return JENGA_ERR_INVALID;
+  // a sliding-window kind keeps only the pages of its window resident: a wider view would read
+  // pages the allocator has already handed to someone else
+  if (k.desc.type == JENGA_WINDOW && (window <= 0 || window > k.desc.window)) return JENGA_ERR_INVALID;
   if (batch > kMaxBatch) return JENGA_ERR_UNSUPPORTED;
   if (n_q_heads % k.desc.n_kv_heads != 0) return JENGA_ERR_INVALID;
   const int G = n_q_heads / k.desc.n_kv_heads;

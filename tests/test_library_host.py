@@ -234,3 +234,9 @@ def test_partition_geometry_and_workspace_queries():
     assert e.value.status == -6
     with pytest.raises(J.JengaError):
         lib.decode_workspace_bytes(0, 16, 64, 8193, pages_per_split=-1)
+    # a sliding-window kind cannot be read with a wider window than it keeps resident
+    assert lib.decode_workspace_bytes(1, 16, 64, 8193, window=1000) > 0
+    for bad in (0, 4097):
+        with pytest.raises(J.JengaError) as e:
+            lib.decode_workspace_bytes(1, 16, 64, 8193, window=bad)
+        assert e.value.status == -1
