@@ -313,25 +313,29 @@ DecodeFn pick_d(int D, bool mat, bool quad, int G) {
 
 // Partitions of the automatic mode: resident blocks of `fn`, at most one per SIMD, a multiple
 // of 8 (one share per XCD), capped at kMaxPartitions.  Cached per kernel; 2048 when no device can be asked.
-int resident_partitions(DecodeFn fn) {
-  static std::mutex mu;
-  static std::unordered_map<const void*, int> cache;
-  std::lock_guard<std::mutex> lock(mu);
-  auto it = cache.find(reinterpret_cast<const void*>(fn));
-  if (it != cache.end()) return it->second;
+int resident_partitions(DecodeFn fn) noexcept {
   int n = 2048;
-  int dev = 0, cus = 0, per_cu = 0;
-  if (hipGetDevice(&dev) == hipSuccess &&
-      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess &&
-      hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kWave, 0) == hipSuccess &&
-      cus > 0 && per_cu > 0) {
-    // one wavefront per SIMD (4 per compute unit): measured faster than filling every slot,
-    // and it leaves each wavefront the registers for a deep load pipeline
-    n = std::min(kMaxPartitions, cus * std::min(per_cu, 4)) / 8 * 8;
-    n = std::max(n, 8);
-    cache.emplace(reinterpret_cast<const void*>(fn), n);
-  } else {
-    (void)hipGetLastError();      // no device: do not leave a sticky error, do not cache
+  try {
+    static std::mutex mu;
+    static std::unordered_map<const void*, int> cache;
+    std::lock_guard<std::mutex> lock(mu);
+    auto it = cache.find(reinterpret_cast<const void*>(fn));
+    if (it != cache.end()) return it->second;
+    int dev = 0, cus = 0, per_cu = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess &&
+        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kWave, 0) == hipSuccess &&
+        cus > 0 && per_cu > 0) {
+      // one wavefront per SIMD (4 per compute unit): measured faster than filling every slot,
+      // and it leaves each wavefront the registers for a deep load pipeline
+      n = std::min(kMaxPartitions, cus * std::min(per_cu, 4)) / 8 * 8;
+      n = std::max(n, 8);
+      cache.emplace(reinterpret_cast<const void*>(fn), n);
+    } else {
+      (void)hipGetLastError();      // no device: do not leave a sticky error, do not cache
+    }
+  } catch (...) {
+    // out of host memory while caching: the value is still right, it is just not remembered
   }
   return n;
 }

@@ -5,6 +5,7 @@
 #include <algorithm>
 #include <cstring>
 #include <limits>
+#include <memory>
 #include <new>
 #include <numeric>
 
@@ -66,19 +67,17 @@ inline bool bit_get(const std::vector<uint64_t>& v, int64_t i) { return (v[i >> 
 inline void bit_set(std::vector<uint64_t>& v, int64_t i) { v[i >> 6] |= uint64_t(1) << (i & 63); }
 inline void bit_clear(std::vector<uint64_t>& v, int64_t i) { v[i >> 6] &= ~(uint64_t(1) << (i & 63)); }
 
-// Lowest clear bit in [begin, end), or -1.
-int64_t first_clear(const std::vector<uint64_t>& v, int64_t begin, int64_t end) {
-  int64_t i = begin;
-  while (i < end) {
-    const int64_t w = i >> 6;
-    uint64_t inv = ~v[w];
-    inv &= ~uint64_t(0) << (i & 63);
-    const int64_t word_end = (w + 1) << 6;
-    if (word_end > end) inv &= (uint64_t(1) << (end & 63)) - 1;
-    if (inv) return (w << 6) + __builtin_ctzll(inv);
-    i = word_end;
+// No exception may cross the C ABI: every entry point below runs its body through this.  The
+// containers of the pool can only throw when host memory runs out, reported as JENGA_ERR_OOM.
+template <class F>
+int guarded(F&& body) noexcept {
+  try {
+    return body();
+  } catch (const std::bad_alloc&) {
+    return JENGA_ERR_OOM;
+  } catch (...) {
+    return JENGA_ERR_INVALID;
   }
-  return -1;
 }
 
 bool kind_ok(const jenga_pool* p, int32_t kind) { return p && kind >= 0 && kind < int32_t(p->kinds.size()); }
@@ -306,6 +305,7 @@ int free_small(jenga_pool* p, int32_t kind, int32_t sid) { return release_small(
 extern "C" {
 
 int jenga_lcm_page_bytes(const jenga_kind_desc* kinds, int32_t n_kinds, int64_t* out_bytes) {
+  return guarded([&]() -> int {
   if (!kinds || n_kinds < 1 || !out_bytes) return JENGA_ERR_INVALID;
   std::vector<Kind> ks(n_kinds);
   for (int32_t i = 0; i < n_kinds; ++i) {
@@ -313,24 +313,26 @@ int jenga_lcm_page_bytes(const jenga_kind_desc* kinds, int32_t n_kinds, int64_t*
     if (rc != JENGA_OK) return rc;
   }
   return lcm_of(ks, out_bytes);
+  });
 }
 
 int jenga_pool_create(void* device_base, int64_t pool_bytes, int64_t large_page_bytes,
                       const jenga_kind_desc* kinds, int32_t n_kinds, jenga_pool** out) {
+  return guarded([&]() -> int {
   if (!kinds || n_kinds < 1 || !out || pool_bytes < 0 || large_page_bytes <= 0) return JENGA_ERR_INVALID;
   *out = nullptr;
   if (reinterpret_cast<uintptr_t>(device_base) % 256 != 0) return JENGA_ERR_ALIGN;
-  jenga_pool* p = new (std::nothrow) jenga_pool();
+  std::unique_ptr<jenga_pool> p(new (std::nothrow) jenga_pool());
   if (!p) return JENGA_ERR_OOM;
   p->kinds.resize(n_kinds);
   for (int32_t i = 0; i < n_kinds; ++i) {
     const int rc = derive_kind(kinds[i], &p->kinds[i]);
-    if (rc != JENGA_OK) { delete p; return rc; }
+    if (rc != JENGA_OK) return rc;
   }
   int64_t lcm = 0;
   int rc = lcm_of(p->kinds, &lcm);
-  if (rc != JENGA_OK) { delete p; return rc; }
-  if (large_page_bytes % lcm != 0) { delete p; return JENGA_ERR_INVALID; }
+  if (rc != JENGA_OK) return rc;
+  if (large_page_bytes % lcm != 0) return JENGA_ERR_INVALID;
   p->base = static_cast<char*>(device_base);
   p->pool_bytes = pool_bytes;
   p->large_bytes = large_page_bytes;
@@ -338,10 +340,8 @@ int jenga_pool_create(void* device_base, int64_t pool_bytes, int64_t large_page_
   for (Kind& k : p->kinds) {
     k.per_large = large_page_bytes / k.small_bytes;
     if (k.per_large > std::numeric_limits<int32_t>::max() ||
-        p->n_large * k.per_large > std::numeric_limits<int32_t>::max()) {
-      delete p;
+        p->n_large * k.per_large > std::numeric_limits<int32_t>::max())
       return JENGA_ERR_UNSUPPORTED;      // small ids are int32
-    }
     k.used.assign(size_t((p->n_large * k.per_large + 63) / 64), 0);
     k.cached.assign(k.used.size(), 0);
   }
@@ -352,8 +352,9 @@ int jenga_pool_create(void* device_base, int64_t pool_bytes, int64_t large_page_
   p->large_cached.assign(size_t(p->n_large), 0);
   p->evictable_large_key.assign(size_t(p->n_large), std::make_tuple(int64_t(0), int64_t(0), int64_t(-1)));
   for (int64_t i = 0; i < p->n_large; ++i) p->free_large.insert(p->free_large.end(), i);
-  *out = p;
+  *out = p.release();
   return JENGA_OK;
+  });
 }
 
 int jenga_pool_destroy(jenga_pool* pool) {
@@ -363,22 +364,29 @@ int jenga_pool_destroy(jenga_pool* pool) {
 }
 
 int jenga_alloc_small(jenga_pool* pool, int32_t kind, int64_t request, int32_t* out_small_id) {
+  return guarded([&]() -> int {
   if (!kind_ok(pool, kind) || !out_small_id) return JENGA_ERR_INVALID;
   return alloc_small(pool, kind, request, out_small_id, nullptr);
+  });
 }
 
 int jenga_ref_small(jenga_pool* pool, int32_t kind, int32_t small_id) {
+  return guarded([&]() -> int {
   if (!kind_ok(pool, kind) || !small_live(pool, kind, small_id)) return JENGA_ERR_INVALID;
   ++pool->kinds[kind].extra_refs[small_id];
   return JENGA_OK;
+  });
 }
 
 int jenga_free_small(jenga_pool* pool, int32_t kind, int32_t small_id) {
+  return guarded([&]() -> int {
   if (!kind_ok(pool, kind)) return JENGA_ERR_INVALID;
   return free_small(pool, kind, small_id);
+  });
 }
 
 int jenga_pool_get_info(const jenga_pool* pool, jenga_pool_info* out) {
+  return guarded([&]() -> int {
   if (!pool || !out) return JENGA_ERR_INVALID;
   out->large_page_bytes = pool->large_bytes;
   out->n_large_pages = pool->n_large;
@@ -386,9 +394,11 @@ int jenga_pool_get_info(const jenga_pool* pool, jenga_pool_info* out) {
   out->n_kinds = int32_t(pool->kinds.size());
   out->reserved = 0;
   return JENGA_OK;
+  });
 }
 
 int jenga_pool_kind_stats(const jenga_pool* pool, int32_t kind, jenga_kind_stats* out) {
+  return guarded([&]() -> int {
   if (!kind_ok(pool, kind) || !out) return JENGA_ERR_INVALID;
   const Kind& k = pool->kinds[kind];
   out->small_page_bytes = k.small_bytes;
@@ -399,18 +409,22 @@ int jenga_pool_kind_stats(const jenga_pool* pool, int32_t kind, jenga_kind_stats
   out->unused_small_pages = k.owned_large * k.per_large - k.used_small - k.cached_small;
   out->evictable_small_pages = k.cached_small;
   return JENGA_OK;
+  });
 }
 
 int jenga_large_page_owner(const jenga_pool* pool, int64_t large_page, int32_t* out_kind,
                            int64_t* out_request) {
+  return guarded([&]() -> int {
   if (!pool || large_page < 0 || large_page >= pool->n_large || !out_kind || !out_request)
     return JENGA_ERR_INVALID;
   *out_kind = pool->large_kind[large_page];
   *out_request = pool->large_request[large_page];
   return JENGA_OK;
+  });
 }
 
 int jenga_small_refcount(const jenga_pool* pool, int32_t kind, int32_t small_id, int32_t* out) {
+  return guarded([&]() -> int {
   if (!kind_ok(pool, kind) || !out) return JENGA_ERR_INVALID;
   const Kind& k = pool->kinds[kind];
   if (small_id < 0 || int64_t(small_id) >= pool->n_large * k.per_large) return JENGA_ERR_INVALID;
@@ -418,10 +432,12 @@ int jenga_small_refcount(const jenga_pool* pool, int32_t kind, int32_t small_id,
   auto it = k.extra_refs.find(small_id);
   *out = 1 + (it == k.extra_refs.end() ? 0 : it->second);
   return JENGA_OK;
+  });
 }
 
 int jenga_kv_offset(const jenga_pool* pool, int32_t kind, int32_t small_id, int32_t layer,
                     int32_t kv_head, int32_t is_v, int32_t token_in_page, int64_t* out_bytes) {
+  return guarded([&]() -> int {
   if (!kind_ok(pool, kind) || !out_bytes) return JENGA_ERR_INVALID;
   const Kind& k = pool->kinds[kind];
   if (!is_attention(k.desc.type)) return JENGA_ERR_INVALID;
@@ -434,9 +450,11 @@ int jenga_kv_offset(const jenga_pool* pool, int32_t kind, int32_t small_id, int3
   *out_bytes = int64_t(small_id) * k.small_bytes + int64_t(layer) * k.slice_bytes +
                int64_t(kv_head) * 2 * plane + int64_t(is_v) * plane + int64_t(token_in_page) * row;
   return JENGA_OK;
+  });
 }
 
 int jenga_request_extend(jenga_pool* pool, int64_t request, int32_t kind, int64_t new_len) {
+  return guarded([&]() -> int {
   if (!kind_ok(pool, kind) || new_len < 0) return JENGA_ERR_INVALID;
   const Kind& k = pool->kinds[kind];
   const int64_t T = k.desc.tokens_per_page;
@@ -467,10 +485,12 @@ int jenga_request_extend(jenga_pool* pool, int64_t request, int32_t kind, int64_
     }
   }
   return JENGA_OK;
+  });
 }
 
 int jenga_request_share_prefix(jenga_pool* pool, int64_t src_request, int64_t dst_request,
                                int32_t kind, int32_t n_pages) {
+  return guarded([&]() -> int {
   if (!kind_ok(pool, kind) || n_pages < 0 || src_request == dst_request) return JENGA_ERR_INVALID;
   auto src = pool->requests.find(src_request);
   if (src == pool->requests.end() || int64_t(src->second.pages[kind].size()) < n_pages)
@@ -489,9 +509,11 @@ int jenga_request_share_prefix(jenga_pool* pool, int64_t src_request, int64_t ds
     dst.pages[kind].push_back(s[p]);
   }
   return JENGA_OK;
+  });
 }
 
 int jenga_request_free(jenga_pool* pool, int64_t request) {
+  return guarded([&]() -> int {
   if (!pool) return JENGA_ERR_INVALID;
   auto it = pool->requests.find(request);
   if (it == pool->requests.end()) return JENGA_ERR_INVALID;
@@ -500,17 +522,21 @@ int jenga_request_free(jenga_pool* pool, int64_t request) {
       if (sid >= 0) free_small(pool, int32_t(kind), sid);
   pool->requests.erase(it);
   return JENGA_OK;
+  });
 }
 
 int jenga_request_num_pages(const jenga_pool* pool, int64_t request, int32_t kind, int32_t* out) {
+  return guarded([&]() -> int {
   if (!kind_ok(pool, kind) || !out) return JENGA_ERR_INVALID;
   auto it = pool->requests.find(request);
   *out = it == pool->requests.end() ? 0 : int32_t(it->second.pages[kind].size());
   return JENGA_OK;
+  });
 }
 
 int jenga_request_block_table_row(const jenga_pool* pool, int64_t request, int32_t kind,
                                   int32_t* row, int32_t width) {
+  return guarded([&]() -> int {
   if (!kind_ok(pool, kind) || !row || width < 0) return JENGA_ERR_INVALID;
   auto it = pool->requests.find(request);
   size_t n = 0;
@@ -522,20 +548,24 @@ int jenga_request_block_table_row(const jenga_pool* pool, int64_t request, int32
   }
   std::fill(row + n, row + width, -1);
   return JENGA_OK;
+  });
 }
 
 int jenga_requests_extend(jenga_pool* pool, int32_t kind, const int64_t* requests,
                           const int64_t* new_lens, int32_t n) {
+  return guarded([&]() -> int {
   if (!kind_ok(pool, kind) || n < 0 || (n > 0 && (!requests || !new_lens))) return JENGA_ERR_INVALID;
   for (int32_t i = 0; i < n; ++i) {
     const int rc = jenga_request_extend(pool, requests[i], kind, new_lens[i]);
     if (rc != JENGA_OK) return rc;
   }
   return JENGA_OK;
+  });
 }
 
 int jenga_block_table_fill(const jenga_pool* pool, int32_t kind, const int64_t* requests, int32_t n,
                            int32_t* table, int32_t width) {
+  return guarded([&]() -> int {
   if (!kind_ok(pool, kind) || n < 0 || width < 0 || (n > 0 && (!requests || !table)))
     return JENGA_ERR_INVALID;
   for (int32_t i = 0; i < n; ++i) {
@@ -543,24 +573,30 @@ int jenga_block_table_fill(const jenga_pool* pool, int32_t kind, const int64_t* 
     if (rc != JENGA_OK) return rc;
   }
   return JENGA_OK;
+  });
 }
 
 int jenga_alloc_small_evict(jenga_pool* pool, int32_t kind, int64_t request, int32_t* out_small_id,
                             int32_t* evicted_kinds, int32_t* evicted_ids, int32_t capacity,
                             int32_t* out_n_evicted) {
+  return guarded([&]() -> int {
   if (!kind_ok(pool, kind) || !out_small_id || capacity < 0) return JENGA_ERR_INVALID;
   Evicted ev{evicted_kinds, evicted_ids, capacity, 0};
   const int rc = alloc_small(pool, kind, request, out_small_id, &ev);
   if (out_n_evicted) *out_n_evicted = ev.n;
   return rc;
+  });
 }
 
 int jenga_release_small(jenga_pool* pool, int32_t kind, int32_t small_id, int32_t keep_cached) {
+  return guarded([&]() -> int {
   if (!kind_ok(pool, kind)) return JENGA_ERR_INVALID;
   return release_small(pool, kind, small_id, keep_cached != 0);
+  });
 }
 
 int jenga_acquire_cached(jenga_pool* pool, int32_t kind, int32_t small_id) {
+  return guarded([&]() -> int {
   if (!kind_ok(pool, kind) || !small_in_range(pool, kind, small_id)) return JENGA_ERR_INVALID;
   Kind& k = pool->kinds[kind];
   if (!bit_get(k.cached, small_id)) return JENGA_ERR_INVALID;
@@ -575,6 +611,7 @@ int jenga_acquire_cached(jenga_pool* pool, int32_t kind, int32_t small_id) {
   ++pool->large_used[large];
   if (was_evictable) refresh_evictable_large(pool, large);
   return JENGA_OK;
+  });
 }
 
 namespace {
@@ -596,22 +633,29 @@ int set_key(jenga_pool* pool, int32_t kind, int32_t sid, bool is_time, int64_t v
 }  // namespace
 
 int jenga_set_last_access(jenga_pool* pool, int32_t kind, int32_t small_id, int64_t time) {
+  return guarded([&]() -> int {
   return set_key(pool, kind, small_id, true, time);
+  });
 }
 
 int jenga_set_prefix_length(jenga_pool* pool, int32_t kind, int32_t small_id, int64_t length) {
+  return guarded([&]() -> int {
   return set_key(pool, kind, small_id, false, length);
+  });
 }
 
 int jenga_small_state(const jenga_pool* pool, int32_t kind, int32_t small_id, int32_t* out_state) {
+  return guarded([&]() -> int {
   if (!kind_ok(pool, kind) || !small_in_range(pool, kind, small_id) || !out_state) return JENGA_ERR_INVALID;
   const Kind& k = pool->kinds[kind];
   *out_state = bit_get(k.used, small_id) ? JENGA_PAGE_USED
                : bit_get(k.cached, small_id) ? JENGA_PAGE_EVICTABLE : JENGA_PAGE_EMPTY;
   return JENGA_OK;
+  });
 }
 
 int jenga_request_release(jenga_pool* pool, int64_t request, int32_t keep_cached) {
+  return guarded([&]() -> int {
   if (!pool) return JENGA_ERR_INVALID;
   auto it = pool->requests.find(request);
   if (it == pool->requests.end()) return JENGA_ERR_INVALID;
@@ -620,10 +664,12 @@ int jenga_request_release(jenga_pool* pool, int64_t request, int32_t keep_cached
       if (sid >= 0) release_small(pool, int32_t(kind), sid, keep_cached != 0);
   pool->requests.erase(it);
   return JENGA_OK;
+  });
 }
 
 int jenga_request_touch(jenga_pool* pool, int64_t request, int32_t kind, int64_t first_token,
                         int64_t end_token, int64_t time) {
+  return guarded([&]() -> int {
   if (!kind_ok(pool, kind) || first_token < 0 || end_token < first_token) return JENGA_ERR_INVALID;
   auto it = pool->requests.find(request);
   if (it == pool->requests.end()) return JENGA_ERR_INVALID;
@@ -633,9 +679,11 @@ int jenga_request_touch(jenga_pool* pool, int64_t request, int32_t kind, int64_t
   for (int64_t pg = first_token / T; pg < p_end; ++pg)
     if (lst[pg] >= 0) set_key(pool, kind, lst[pg], true, time);
   return JENGA_OK;
+  });
 }
 
 int jenga_request_set_prefix_lengths(jenga_pool* pool, int64_t request, int32_t kind) {
+  return guarded([&]() -> int {
   if (!kind_ok(pool, kind)) return JENGA_ERR_INVALID;
   auto it = pool->requests.find(request);
   if (it == pool->requests.end()) return JENGA_ERR_INVALID;
@@ -644,10 +692,12 @@ int jenga_request_set_prefix_lengths(jenga_pool* pool, int64_t request, int32_t 
   for (size_t pg = 0; pg < lst.size(); ++pg)
     if (lst[pg] >= 0) set_key(pool, kind, lst[pg], false, int64_t(pg + 1) * T);
   return JENGA_OK;
+  });
 }
 
 int jenga_possible_prefixes(int32_t rule, int32_t param, const uint8_t* is_hit, int32_t n_tokens,
                             uint8_t* out_valid) {
+  return guarded([&]() -> int {
   if (n_tokens < 0 || (n_tokens > 0 && !is_hit) || !out_valid) return JENGA_ERR_INVALID;
   if ((rule == JENGA_HIT_WINDOW || rule == JENGA_HIT_EVERY) && param < 1) return JENGA_ERR_INVALID;
   out_valid[0] = 0;
@@ -674,9 +724,11 @@ int jenga_possible_prefixes(int32_t rule, int32_t param, const uint8_t* is_hit, 
     default:
       return JENGA_ERR_INVALID;
   }
+  });
 }
 
 int jenga_longest_common_prefix(const uint8_t* const* valid_sets, int32_t n_sets, int32_t n_tokens) {
+  return guarded([&]() -> int {
   if (!valid_sets || n_sets < 1 || n_tokens < 0) return JENGA_ERR_INVALID;
   for (int32_t p = n_tokens; p >= 1; --p) {
     bool all = true;
@@ -684,6 +736,7 @@ int jenga_longest_common_prefix(const uint8_t* const* valid_sets, int32_t n_sets
     if (all) return p;
   }
   return 0;
+  });
 }
 
 const char* jenga_strerror(int status) {
