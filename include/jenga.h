@@ -50,7 +50,7 @@ typedef void* jenga_stream;             /* a hipStream_t, or NULL for the null s
 typedef enum {
   JENGA_OK = 0,
   JENGA_ERR_INVALID = -1,    /* bad argument, unknown id, double free, wrong kind type */
-  JENGA_ERR_OOM = -2,        /* allocation steps 1-3 all failed (no eviction on this path) */
+  JENGA_ERR_OOM = -2,        /* no page: every allocation step failed; also host memory exhausted */
   JENGA_ERR_ALIGN = -3,      /* a pointer or size is not 16-byte aligned */
   JENGA_ERR_WORKSPACE = -4,  /* split-K workspace too small */
   JENGA_ERR_HIP = -5,        /* a HIP runtime call failed */
