@@ -114,6 +114,26 @@ def cpu_baseline(runner, budget_s: float):
     }
 
 
+def stream_read_rate(pool_u8, nbytes: int = 8 << 30, reps: int = 5) -> float:
+    """GB/s of the library's plain non-temporal read stream over the first bytes of the pool:
+    the rate the memory system gives a kernel that does nothing but read."""
+    import torch
+    import paper_2503_18292_amd as J
+    n = min(nbytes, pool_u8.numel()) // 4096 * 4096
+    if n == 0:
+        return 0.0
+    sink = torch.zeros(4, dtype=torch.int32, device=pool_u8.device)
+    J.stream_read(pool_u8, n, sink)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        J.stream_read(pool_u8, n, sink)
+    e1.record()
+    torch.cuda.synchronize()
+    return n * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+
+
 def copy_calibration(gib: float):
     """Known traffic for counter calibration: copy reads N and writes N bytes, read reads N."""
     import torch
@@ -316,6 +336,8 @@ def main():
         torch.cuda.synchronize()
         ms_per_step_events = (time.perf_counter() - t2) / args.steps * 1e3
 
+    # what a plain read stream gets from the same memory, measured after the timed regions
+    stream_gbs = stream_read_rate(r.pool_u8) if use_events else 0.0
     roof = {"bound": "hbm", "achieved": None, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": None,
             "traffic": None, "kernel": "decode_partial_kernel"}
     if use_events:
@@ -339,6 +361,8 @@ def main():
             "median_launch_us": round(float(np.median(launch_ms)) * 1e3, 2),
             "min_launch_us": round(min(launch_ms) * 1e3, 2),
             "ms_per_step_with_events": round(ms_per_step_events, 3),
+            "stream_read_GBps": round(stream_gbs, 1),
+            "frac_of_stream_read": round(achieved / stream_gbs, 4) if stream_gbs > 0 else None,
             "algorithmic_bytes_per_launch": round(k_bytes / n_launch),
             "traffic": (round(MEASURED_TRAFFIC[cfg.name]["fetch_over_algorithmic"] * k_bytes / n_launch
                               + MEASURED_TRAFFIC[cfg.name]["write_bytes"])

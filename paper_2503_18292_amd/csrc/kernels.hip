@@ -248,14 +248,43 @@ __global__ __launch_bounds__(256) void stream_copy_kernel(u32x4* __restrict__ ds
     __builtin_nontemporal_store(__builtin_nontemporal_load(src + i), dst + i);
 }
 
-__global__ __launch_bounds__(256) void stream_read_kernel(const u32x4* __restrict__ src, int64_t n,
-                                                          unsigned* __restrict__ sink) {
-  const int64_t stride = int64_t(gridDim.x) * blockDim.x;
+// A read stream shaped like the decode kernel's: one wavefront per block, 16 KiB (16 loads of
+// 16 bytes per lane) per step, the next step's loads issued before this step's are used.  Its
+// rate is what the memory system gives a kernel that does nothing but read.
+__global__ __launch_bounds__(kWave) void stream_read_kernel(const u32x4* __restrict__ src, int64_t n,
+                                                            unsigned* __restrict__ sink) {
+  constexpr int kLoads = 16;
+  constexpr int64_t kChunk = int64_t(kLoads) * kWave;          // 16-byte units per step
+  const int lane = threadIdx.x;
+  const int64_t n_chunks = n / kChunk;
   unsigned x = 0;
-  for (int64_t i = int64_t(blockIdx.x) * blockDim.x + threadIdx.x; i < n; i += stride) {
-    const u32x4 v = __builtin_nontemporal_load(src + i);
-    x ^= v.x ^ v.y ^ v.z ^ v.w;
+  u32x4 v[2][kLoads];
+  auto issue = [&](int64_t c, u32x4* buf) {
+    const u32x4* p = src + c * kChunk + lane;
+#pragma unroll
+    for (int u = 0; u < kLoads; ++u) buf[u] = __builtin_nontemporal_load(p + u * kWave);
+  };
+  auto use = [&](const u32x4* buf) {
+#pragma unroll
+    for (int u = 0; u < kLoads; ++u) x ^= buf[u].x ^ buf[u].y ^ buf[u].z ^ buf[u].w;
+  };
+  int64_t c = blockIdx.x;
+  if (c < n_chunks) issue(c, v[0]);
+  while (c < n_chunks) {
+    const int64_t c1 = c + gridDim.x;
+    if (c1 < n_chunks) issue(c1, v[1]);
+    use(v[0]);
+    if (c1 >= n_chunks) break;
+    const int64_t c2 = c1 + gridDim.x;
+    if (c2 < n_chunks) issue(c2, v[0]);
+    use(v[1]);
+    c = c2;
   }
+  if (blockIdx.x == 0)                                         // what does not fill a whole step
+    for (int64_t i = n_chunks * kChunk + lane; i < n; i += kWave) {
+      const u32x4 t = __builtin_nontemporal_load(src + i);
+      x ^= t.x ^ t.y ^ t.z ^ t.w;
+    }
   if (x == 0x9e3779b9u) *sink = x;     // practically never taken; keeps the loads alive
 }
 
@@ -609,8 +638,9 @@ int jenga_stream_read(const void* src, int64_t bytes, void* sink, jenga_stream s
   if (!aligned16(src)) return JENGA_ERR_ALIGN;
   if (bytes == 0) return JENGA_OK;
   const int64_t n = bytes / 16;
-  const unsigned blocks = unsigned(std::min<int64_t>((n + 255) / 256, 256 * 32));
-  hipLaunchKernelGGL(stream_read_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
+  // one wavefront per SIMD of a 256-unit device, fewer for short streams
+  const unsigned blocks = unsigned(std::max<int64_t>(1, std::min<int64_t>(n / (16 * kWave), 1024)));
+  hipLaunchKernelGGL(stream_read_kernel, dim3(blocks), dim3(kWave), 0, static_cast<hipStream_t>(stream),
                      static_cast<const u32x4*>(src), n, static_cast<unsigned*>(sink));
   return hip_status();
 }
