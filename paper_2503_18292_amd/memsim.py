@@ -58,16 +58,23 @@ def make_trace(kind: str, n_requests: int, max_len: int, seed: int):
     return out
 
 
-def simulate(model: str, trace_kind: str, n_requests: int = 24, pool_gib: float = 64.0,
+def simulate(model: str, trace_kind: str, n_requests: int = 24, pool_gib: float = 0.0,
              tokens_per_page: int = 16, seed: int = 0, sample_every: int = 16):
+    """pool_gib <= 0: a pool that holds every request of the trace at its final length at once
+    (the simulation is about waste, not about running out of pages)."""
     m = MODELS[model]
     kinds = [make_kind(k.type, api.BF16, k.n_layers, m["n_kv_heads"], m["head_dim"], tokens_per_page, k.window)
              for k in m["kinds"]]
     per_tok_layer = 2 * m["n_kv_heads"] * m["head_dim"] * 2
     large = api.lcm_page_bytes(kinds)
-    pool = Pool(None, int(pool_gib * 2**30), kinds, large)
     n_layers = sum(k.n_layers for k in m["kinds"])
     trace = make_trace(trace_kind, n_requests, m["max_len"], seed)
+    if pool_gib > 0:
+        pool_bytes = int(pool_gib * 2**30)
+    else:
+        final = sum(prompt + out_len + tokens_per_page for _, prompt, out_len in trace)
+        pool_bytes = int(1.05 * final * n_layers * per_tok_layer) + 64 * large
+    pool = Pool(None, pool_bytes, kinds, large)
     horizon = max(a + o for a, _, o in trace) + 1
     length = {}                                   # live request -> cached tokens
     rows = []
@@ -114,7 +121,7 @@ def main():
     ap.add_argument("--model", default="ministral_like", choices=sorted(MODELS))
     ap.add_argument("--trace", default="dynamic", choices=["static", "dynamic"])
     ap.add_argument("--requests", type=int, default=24)
-    ap.add_argument("--pool-gib", type=float, default=64.0)
+    ap.add_argument("--pool-gib", type=float, default=0.0, help="0: sized from the trace")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--timeline", action="store_true", help="also print one JSON line per sample")
     a = ap.parse_args()
