@@ -33,10 +33,6 @@ struct QuadEngine {
   static constexpr int V_OFF = T * ROW;                // K rows come first in a (page, head) block
   static constexpr int kTileLog2 = PPT == 1 ? 4 : PPT == 2 ? 5 : 6;
   static constexpr int kLdsFloats = 2 * PPT * T * G;   // softmax weights of a tile, double buffered
-  // Pipeline depth, see run().  Measured: with 4 query heads per KV head the deeper pipeline is
-  // worth +6 % although some of its registers spill to accumulation registers; with 2 heads
-  // both depths run at the same speed.
-  static constexpr int kAhead = 1;
   static_assert(KCH >= 2 && KCH <= 8, "row size");
 
   __device__ __forceinline__ static void run(const DecodeParams& p, int lane, int b, int kvh, int L, int tile0,
@@ -93,24 +89,21 @@ struct QuadEngine {
       }
     };
 
-    // Software pipeline.  AHEAD = 1 (two tiles deep): while tile t is computed, K(t+1), V(t+1)
-    // and (after the scores) K(t+2) are in flight, 16 to 32 KiB per wavefront.  AHEAD = 0: V(t)
-    // is issued at the start of tile t and K(t+1) after the scores, 8 to 16 KiB in flight (kept
-    // for comparison; not the configuration that is built).
-    // Loads return in order, so waiting for the oldest tile leaves the younger ones outstanding.
-    constexpr int AHEAD = kAhead;
-    u32x4 kb[1 + AHEAD][NLD], vb[1 + AHEAD][NLD];
+    // Software pipeline, two tiles deep: while tile t is computed, K(t+1), V(t+1) and (after the
+    // scores) K(t+2) are in flight, 16 to 32 KiB per wavefront.  Loads return in order, so
+    // waiting for the oldest tile leaves the younger ones outstanding.  (Issuing V(t) only at the
+    // start of tile t and K(t+1) after the scores measured the same with 2 query heads per KV
+    // head and 6 % slower with 4.)
+    u32x4 kb[2][NLD], vb[2][NLD];
     load_pages(0, k_voff, 64, kb[0]);
-    if (AHEAD) {
-      load_pages(0, v_voff, 1024, vb[0]);
-      if (n_tiles > 1) {
-        load_pages(1, k_voff, 64, kb[AHEAD]);
-        ids.k_stream_at(PPT);
-      }
+    load_pages(0, v_voff, 1024, vb[0]);
+    if (n_tiles > 1) {
+      load_pages(1, k_voff, 64, kb[1]);
+      ids.k_stream_at(PPT);
     }
 
     auto step = [&](int tile, u32x4* kbuf, u32x4* vbuf, u32x4* v_next) {
-      if (tile + AHEAD < n_tiles) load_pages(tile + AHEAD, v_voff, 1024, v_next);
+      if (tile + 1 < n_tiles) load_pages(tile + 1, v_voff, 1024, v_next);
 
       // Fused append: the wavefront whose chunk holds the tile of the newest token (position
       // L - 1) takes that token's rows from k_new / v_new instead of the pool and stores them
@@ -164,9 +157,9 @@ struct QuadEngine {
           s[pp][g] = x * p.scale_log2;
         }
 
-      if (tile + 1 + AHEAD < n_tiles) {
-        load_pages(tile + 1 + AHEAD, k_voff, 64, kbuf);
-        ids.k_stream_at((tile + 1 + AHEAD) * PPT);
+      if (tile + 2 < n_tiles) {
+        load_pages(tile + 2, k_voff, 64, kbuf);
+        ids.k_stream_at((tile + 2) * PPT);
       }
 
       const int tile_tok = tok0 + tile * PPT * T;           // first token of the tile
@@ -227,13 +220,9 @@ struct QuadEngine {
       __builtin_amdgcn_wave_barrier();
     };
 
-    if (AHEAD) {
-      for (int tile = 0; tile < n_tiles; tile += 2) {
-        step(tile, kb[0], vb[0], vb[AHEAD]);
-        if (tile + 1 < n_tiles) step(tile + 1, kb[AHEAD], vb[AHEAD], vb[0]);
-      }
-    } else {
-      for (int tile = 0; tile < n_tiles; ++tile) step(tile, kb[0], vb[0], vb[0]);
+    for (int tile = 0; tile < n_tiles; tile += 2) {
+      step(tile, kb[0], vb[0], vb[1]);
+      if (tile + 1 < n_tiles) step(tile + 1, kb[1], vb[1], vb[0]);
     }
 
     // every quad of lanes carried the same l; the V lane groups share m, so they just add up
