@@ -39,12 +39,13 @@ def write_contexts_through_library(r, n_chunks=2, pad_rows=3):
     torch.cuda.synchronize()
 
 
-@pytest.mark.parametrize("dtype,D,G,typ,window", [
-    ("bf16", 256, 2, FULL, 0), ("bf16", 128, 4, WINDOW, 100), ("f32", 64, 2, FULL, 0),
-    ("bf16", 128, 4, CROSS, 0), ("f32", 128, 1, WINDOW, 33)])
-def test_write_range_then_decode(dtype, D, G, typ, window):
-    print(f"[case] write_range {dtype} D={D} G={G} {typ} W={window}", flush=True)
-    cfg = custom_cfg(dtype, D, 2 * G, 2, typ, window=window, hi=500, cross_len=333, batch=4)
+@pytest.mark.parametrize("dtype,D,G,typ,window,T", [
+    ("bf16", 256, 2, FULL, 0, 16), ("bf16", 128, 4, WINDOW, 100, 16), ("f32", 64, 2, FULL, 0, 16),
+    ("bf16", 128, 4, CROSS, 0, 16), ("f32", 128, 1, WINDOW, 33, 16), ("bf16", 128, 8, FULL, 0, 64),
+    ("bf16", 64, 16, WINDOW, 150, 32), ("f32", 256, 2, FULL, 0, 8)])
+def test_write_range_then_decode(dtype, D, G, typ, window, T):
+    print(f"[case] write_range {dtype} D={D} G={G} {typ} W={window} T={T}", flush=True)
+    cfg = custom_cfg(dtype, D, 2 * G, 2, typ, window=window, hi=500, cross_len=333, batch=4, T=T)
     r = _runner(cfg, 8)
     r.build_contexts()
     r.host_step()
