@@ -44,3 +44,28 @@ def test_decode_step_in_a_hip_graph(dtype, D, G, typ, window):
         assert torch.equal(r.pool_u8, pool_after)
     check_against_oracle(r, "graph")
     r.close()
+
+
+def test_decode_step_on_a_side_stream():
+    """The kernels run on the stream they are given: a step issued on a non-default stream while
+    the default stream is kept busy gives the eager result."""
+    cfg = custom_cfg("bf16", 128, 8, 2, FULL, lo=100, hi=1200, n_layers=2, batch=5)
+    r = _runner(cfg, 44)
+    prepare(r)
+    r.device_step()
+    torch.cuda.synchronize()
+    eager = {key: v.clone() for key, v in r.out.items()}
+    for v in r.out.values():
+        v.fill_(float("nan"))
+    side = torch.cuda.Stream()
+    busy = torch.zeros(1 << 26, device=r.device)
+    side.wait_stream(torch.cuda.current_stream())
+    for _ in range(20):
+        busy.add_(1.0)                   # the default stream has its own work meanwhile
+    with torch.cuda.stream(side):
+        r.device_step()
+    side.synchronize()
+    for key in eager:
+        assert torch.equal(r.out[key], eager[key]), key
+    torch.cuda.synchronize()
+    r.close()
