@@ -45,7 +45,8 @@ def parse():
     ap.add_argument("--no-kernel-events", action="store_true",
                     help="do not bracket the decode kernel with events (roofline.achieved becomes null)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the oracle timing")
+    ap.add_argument("--cpu-seconds", type=float, default=30.0,
+                    help="wall-clock budget of the CPU-oracle leg (reading slices back, converting, oracle)")
     ap.add_argument("--mode", default="decode", choices=["decode", "kv_write", "allocator"],
                     help="decode: the benchmark proper; kv_write: bulk K/V write of a prefill chunk; "
                          "allocator: host microseconds per allocator call, library against oracle")
@@ -60,7 +61,9 @@ def parse():
 
 
 def cpu_baseline(runner, budget_s: float):
-    """The fp64 oracle on the host cores, on (request, layer) slices gathered from the pool."""
+    """The fp64 oracle on the host cores, on (request, layer) slices gathered from the pool.
+    `budget_s` bounds the wall-clock time of the whole leg (most of it goes into reading the
+    slices back and converting them to fp64); only the oracle's own time enters the rate."""
     import numpy as np
     import torch
     from oracle.attn import decode_attention_one
@@ -71,6 +74,7 @@ def cpu_baseline(runner, budget_s: float):
         threads = 1
     torch.cuda.synchronize()
     t_used, nbytes, n_units, toks = 0.0, 0, 0, 0
+    leg_t0 = time.perf_counter()
     per_kind = {}
     for ki, k in enumerate(runner.attn_kinds):
         kd = runner.cfg.kinds[k]
@@ -79,7 +83,7 @@ def cpu_baseline(runner, budget_s: float):
         for layer in range(kd.n_layers):
             q = runner.inputs[(k, layer)][0].cpu().double().numpy()
             for b in range(runner.cfg.batch):
-                if t_used >= share:
+                if time.perf_counter() - leg_t0 >= share:
                     break
                 K, V = runner.gather(k, layer, b)
                 Kd, Vd = K.double().numpy(), V.double().numpy()
@@ -93,7 +97,7 @@ def cpu_baseline(runner, budget_s: float):
                 t_kind += dt
                 b_kind += vis * kd.bytes_per_token_per_layer
                 n_kind += 1
-            if t_used >= share:
+            if time.perf_counter() - leg_t0 >= share:
                 break
         per_kind[k] = (t_kind, b_kind, n_kind)
         nbytes += b_kind
@@ -107,8 +111,9 @@ def cpu_baseline(runner, budget_s: float):
     return {
         "value": round(gbs, 4), "unit": "GB/s", "cores": int(threads), "kind": "oracle",
         "sample": f"{n_units} (request, layer) slices of the same step, read back from the pool: layers then "
-                  f"requests in order, each attention kind until its share of {budget_s:.0f} s of oracle "
-                  f"time is used; fp64 numpy; scaled to a whole step by bytes and "
+                  f"requests in order, each attention kind until its share of {budget_s:.0f} s of wall-clock "
+                  f"time (read-back and conversion included) is used; fp64 numpy, {t_used:.1f} s inside the oracle; "
+                  f"scaled to a whole step by bytes and "
                   f"layer count: {step_s:.1f} s/step = {runner.cfg.batch / step_s if step_s else 0:.3f} tokens/s",
         "seconds": round(t_used, 2),
     }
