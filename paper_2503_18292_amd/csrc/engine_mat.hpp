@@ -1,11 +1,11 @@
-// Decode engine on the matrix cores: bf16 K/V, pages of 16 tokens or more (see kernels.hip for the front end).
+// Decode engine on the matrix cores: bf16 K/V, any page size (see kernels.hip for the front end).
 #pragma once
 
 #include "decode_common.hpp"
 
 namespace {
 
-// ---- engine for bf16 K/V in pages of 16 tokens or more: both contractions on the matrix cores
+// ---- engine for bf16 K/V: both contractions on the matrix cores ----------------------------
 //
 // The work per 16-token block is a small dense contraction, scores = K[16 x D] . Q^T[D x G] and
 // out += P[G x 16] . V[16 x D], and the matrix cores take it off the vector ALUs altogether:
@@ -31,11 +31,13 @@ namespace {
 // (its rounding and the rounding of the remainder, 16 significant bits together) in two
 // products, so the result stays within fp32 rounding of an fp32 weighted sum -- the matrix
 // cores are idle most of the time anyway.
-template <int D_, int G_>
+// HALF_: the pages hold 8 tokens, half a block (a build of its own, so that the usual case keeps
+// a scalar page address plus a constant lane offset for every load).
+template <int D_, int G_, bool HALF_>
 struct MatEngine {
   using E = BF16;
   static constexpr int D = D_, G = G_;
-  static constexpr int T = 16;                 // tokens per block; a page holds 1, 2, 4 or 8 blocks
+  static constexpr int T = 16;                 // tokens per block; a page holds 1/2, 1, 2, 4 or 8 blocks
   static constexpr int ROW = D * 2;            // bytes per token row
   static constexpr int KCH = ROW / 64;         // k-steps of the score product == 1 KiB loads per page
   static constexpr int PPT = 8 / KCH;          // blocks per tile (1, 2 or 4)
@@ -74,18 +76,22 @@ struct MatEngine {
 
   __device__ __forceinline__ static void run(const DecodeParams& p, int lane, int b, int kvh, int L, int tile0,
                              int n_tiles, int append_tile, int64_t slot, float* lds) {
-    // Pages of 16, 32, 64 or 128 tokens are read as runs of 16-token blocks: block q (counted
-    // from the first visible page) lies in page q >> sh at row offset (q & sub_mask) * 16.
-    const int sh = p.t_log2 - 4;
+    // A 16-token block is the unit of both products.  Pages of 16, 32, 64 or 128 tokens hold 1, 2,
+    // 4 or 8 blocks: block q (counted from the first visible page) lies in page q >> sh at row
+    // (q & sub_mask) * 16.  An 8-token page is half a block: a block takes its rows 0..7 from one
+    // page and its rows 8..15 from the next.
+    constexpr bool t8 = HALF_;
+    const int sh = t8 ? 0 : p.t_log2 - 4;
     const int sub_mask = (1 << sh) - 1;
     int lo_tok, p_lo, p_hi;
     visible_pages(L, p.window, p.t_log2, &lo_tok, &p_lo, &p_hi);
     const int blk0 = tile0 * PPT;                              // first block of the chunk
-    const int page0 = p_lo + (blk0 >> sh);
-    const int off0 = blk0 & sub_mask;                          // its place inside page0
-    const int n_blk = min(n_tiles * PPT, ((p_hi - p_lo) << sh) - blk0);
-    const int n_pages = (off0 + n_blk + sub_mask) >> sh;
-    const int tok0 = ((p_lo << sh) + blk0) * T;
+    const int tot_blk = t8 ? (p_hi - p_lo + 1) >> 1 : (p_hi - p_lo) << sh;
+    const int n_blk = min(n_tiles * PPT, tot_blk - blk0);
+    const int page0 = p_lo + (t8 ? 2 * blk0 : blk0 >> sh);
+    const int off0 = t8 ? 0 : blk0 & sub_mask;                 // place of the first block inside page0
+    const int n_pages = t8 ? min(2 * n_blk, p_hi - page0) : (off0 + n_blk + sub_mask) >> sh;
+    const int tok0 = (p_lo << p.t_log2) + blk0 * T;
     char* v_lds = reinterpret_cast<char*>(lds);
 
     PageIds ids;
@@ -94,8 +100,8 @@ struct MatEngine {
     const int n = lane & 15, j = lane >> 4;
     const int v_row = lane / LPT;                                        // V loads: row v_row + TPL * c of the page
     const char* kv_base = p.layer_base + int64_t(kvh) * p.head_stride;   // wave-uniform
-    const unsigned k_voff = n * ROW + j * 16;                            // A operand of the score product
-    const unsigned v_voff = p.v_offset + lane * 16;
+    const unsigned k_loff = (t8 ? n & 7 : n) * ROW + j * 16;             // A operand of the score product: row n of the block
+    const unsigned v_loff = p.v_offset + v_row * ROW + (lane % LPT) * 16;
     const unsigned lds_wr = v_row * LROW + (lane % LPT) * 16;            // this lane's V bytes (+ row offset)
     const unsigned lds_rd = (4 * j + (n >> 2)) * LROW + (n & 3) * 8;     // transposed read (+ page, + block)
 
@@ -115,57 +121,89 @@ struct MatEngine {
 #pragma unroll
     for (int blk = 0; blk < NBLK; ++blk) acc[blk] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    auto load_pages = [&](int tile, unsigned voff, int step, u32x4* buf) {
+    // Address (wave-uniform) of row 8h of block r of the chunk in this KV head's K rows; the V
+    // rows lie p.v_offset further.  With an odd number of 8-token pages the last block has no
+    // second page: its rows 8..15 are read from the first one again and masked like any token >= L.
+    auto half_base = [&](int r, int h) -> const char* {
+      if (t8) return kv_base + int64_t(ids.get(min(2 * r + h, n_pages - 1))) * p.small_bytes;
+      const int q = off0 + r;
+      return kv_base + int64_t(ids.get(q >> sh)) * p.small_bytes + ((q & sub_mask) * T + 8 * h) * ROW;
+    };
+    auto load_k = [&](int tile, u32x4* buf) {
 #pragma unroll
       for (int pp = 0; pp < PPT; ++pp) {
         const int r = tile * PPT + pp;
         if (PPT == 1 || r < n_blk) {
-          const int q = off0 + r;
-          const char* pb = kv_base + int64_t(ids.get(q >> sh)) * p.small_bytes + (q & sub_mask) * (T * ROW);
+          const char* src = half_base(r, 0) + k_loff;                    // wave-uniform base + lane offset
+          if constexpr (t8) {
+            const char* hi = half_base(r, 1);                            // taken by all lanes: it reads a lane
+            if (n & 8) src = hi + k_loff;
+          }
 #pragma unroll
           for (int c = 0; c < KCH; ++c)
-            buf[pp * KCH + c] =
-                __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(pb + voff + c * step));
+            buf[pp * KCH + c] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + c * 64));
         } else {
 #pragma unroll
           for (int c = 0; c < KCH; ++c) buf[pp * KCH + c] = u32x4{0, 0, 0, 0};
         }
       }
     };
+    auto load_v = [&](int tile, u32x4* buf) {
+#pragma unroll
+      for (int pp = 0; pp < PPT; ++pp) {
+        const int r = tile * PPT + pp;
+        if (PPT == 1 || r < n_blk) {
+          const char* lo = half_base(r, 0);
+          const char* hi = t8 ? half_base(r, 1) : lo + 8 * ROW;
+#pragma unroll
+          for (int c = 0; c < KCH; ++c) {                    // load c covers rows TPL * c .. TPL * c + TPL - 1
+            const char* src = (((TPL * c) & 8) ? hi : lo) + ((TPL * c) & 7) * ROW;     // wave-uniform
+            buf[pp * KCH + c] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + v_loff));
+          }
+        } else {
+#pragma unroll
+          for (int c = 0; c < KCH; ++c) buf[pp * KCH + c] = u32x4{0, 0, 0, 0};
+        }
+      }
+    };
+    // the K stream tells the page-id registers when it enters a new page
+    auto k_entered = [&](int tile) {
+      if (t8) {
+        ids.k_stream_at(2 * tile * PPT);
+      } else {
+        const int q = off0 + tile * PPT;
+        if ((q & sub_mask) == 0) ids.k_stream_at(q >> sh);
+      }
+    };
 
     // two tiles deep, as in the quad engine
     u32x4 kb[2][NLD], vb[2][NLD];
-    load_pages(0, k_voff, 64, kb[0]);
-    load_pages(0, v_voff, 1024, vb[0]);
-    // the K stream tells the page-id registers when it enters a new page
-    auto k_entered = [&](int tile) {
-      const int q = off0 + tile * PPT;
-      if ((q & sub_mask) == 0) ids.k_stream_at(q >> sh);
-    };
+    load_k(0, kb[0]);
+    load_v(0, vb[0]);
     if (n_tiles > 1) {
-      load_pages(1, k_voff, 64, kb[1]);
+      load_k(1, kb[1]);
       k_entered(1);
     }
 
     auto step = [&](int tile, u32x4* kbuf, u32x4* vbuf, u32x4* v_next) {
-      if (tile + 1 < n_tiles) load_pages(tile + 1, v_voff, 1024, v_next);
+      if (tile + 1 < n_tiles) load_v(tile + 1, v_next);
 
       // fused append: rows of the token at L - 1 come from k_new / v_new and are stored into the page
       if (tile == append_tile) {
         const char* kn = static_cast<const char*>(p.k_new) + (int64_t(b) * p.n_kv_heads + kvh) * ROW;
         const char* vn = static_cast<const char*>(p.v_new) + (int64_t(b) * p.n_kv_heads + kvh) * ROW;
-        const int pos = L - 1;
-        const int r_new = (pos >> 4) - ((p_lo << sh) + blk0);     // block of the new token, relative to the chunk
+        const int rel = (L - 1) - (p_lo << p.t_log2);            // the new token, counted from the first visible page
+        const int r_new = (rel >> 4) - blk0;                     // its block, relative to the chunk
+        const int row_new = rel & 15;                            // its row in the block
         const int pp_new = r_new - tile * PPT;
-        const int page_rel = (off0 + r_new) >> sh;
-        char* pb = const_cast<char*>(kv_base) + int64_t(ids.get(page_rel)) * p.small_bytes +
-                   ((off0 + r_new) & sub_mask) * (T * ROW);
+        const int page_rel = t8 ? 2 * r_new + (row_new >> 3) : (off0 + r_new) >> sh;
+        char* dst = const_cast<char*>(half_base(r_new, row_new >> 3)) + (row_new & 7) * ROW;
         const bool store = ids.writable(page_rel);
-        if (n == (pos & 15)) {
+        if (n == row_new) {
 #pragma unroll
           for (int c = 0; c < KCH; ++c) {
             const u32x4 k_app = *reinterpret_cast<const u32x4*>(kn + j * 16 + c * 64);
-            if (store) *reinterpret_cast<u32x4*>(pb + k_voff + c * 64) = k_app;
+            if (store) *reinterpret_cast<u32x4*>(dst + j * 16 + c * 64) = k_app;
 #pragma unroll
             for (int pp = 0; pp < PPT; ++pp)
               if (pp == pp_new) kbuf[pp * KCH + c] = k_app;
@@ -175,12 +213,12 @@ struct MatEngine {
         bool mine = false;
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
-          if ((i / KCH) * T + (i % KCH) * TPL + v_row == pp_new * T + (pos & 15)) {
+          if ((i / KCH) * T + (i % KCH) * TPL + v_row == pp_new * T + row_new) {
             vbuf[i] = v_app;
             mine = true;
           }
         }
-        if (mine && store) *reinterpret_cast<u32x4*>(pb + p.v_offset + (pos & 15) * ROW + (lane % LPT) * 16) = v_app;
+        if (mine && store) *reinterpret_cast<u32x4*>(dst + p.v_offset + (lane % LPT) * 16) = v_app;
       }
 
       // scores: lane (n, j) gets head n, tokens 4j .. 4j+3 of each page
@@ -195,7 +233,7 @@ struct MatEngine {
       }
 
       if (tile + 2 < n_tiles) {
-        load_pages(tile + 2, k_voff, 64, kbuf);
+        load_k(tile + 2, kbuf);
         k_entered(tile + 2);
       }
 

@@ -10,8 +10,8 @@ namespace {
 // K and V are read alike: a token's row is LPT lanes x 16 bytes, one wave-wide load covers
 // TPL = 64 / LPT consecutive tokens (1 KiB, contiguous in the page).  Every partial dot
 // product is summed over LPT lanes, so this engine spends several times more vector-ALU
-// work per byte than the one above; it covers what the other two are not built for (8-token
-// pages; fp32 K/V in pages other than 16 tokens, with 8 query heads per KV head, or 1 KiB rows).  Each group of LPT lanes runs
+// work per byte than the other two; it covers what they are not built for (fp32 K/V in pages
+// other than 16 tokens, with 8 query heads per KV head, or with 1 KiB rows).  Each group of LPT lanes runs
 // its own online softmax over the tokens it sees; the groups are merged once at the end.
 template <typename E_, int D_, int G_>
 struct RowEngine {

@@ -11,11 +11,11 @@
 // is (1) that every wavefront always has KiB-sized loads in flight, (2) that no wavefront
 // idles while others still work (work is cut into equal pieces, not into per-request pieces),
 // and (3) that the arithmetic stays out of the way of the loads.  Three engines share the
-// front end: the matrix-core engine (bf16 K/V, pages of 16 tokens or more: both products of
-// a 16-token block are small dense contractions and go through MFMA, which leaves the vector
-// ALUs almost idle and is what keeps 8 and 16 heads per KV head at the HBM rate), the quad
-// engine (16-token pages on the vector ALUs: fp32 K/V, and 256-element bf16 rows with few
-// heads, where it measures slightly faster), and the general row engine (the rest).
+// front end: the matrix-core engine (bf16 K/V, any page size: both products of a 16-token
+// block are small dense contractions and go through MFMA, which leaves the vector ALUs almost
+// idle and is what keeps 8 and 16 heads per KV head at the HBM rate), the quad engine
+// (16-token pages on the vector ALUs: fp32 K/V, and 256-element bf16 rows with few heads,
+// where it measures slightly faster), and the general row engine (the rest of fp32).
 //
 // The kernel view of the pool is the one of paper Sec. 4.2: a start pointer (pool base +
 // layer offset), a page stride (the kind's small-page size) and page ids (the kind's block
@@ -299,20 +299,22 @@ bool attention_kind(const jenga::Kind& k) {
 bool aligned16(const void* p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; }
 
 // Only the combinations decode_geometry() can ask for are instantiated.
+template <int D, bool HALF>
+DecodeFn pick_mat(int G) {
+  switch (G) {
+    case 1: return decode_partial_kernel<MatEngine<D, 1, HALF>>;
+    case 2: return decode_partial_kernel<MatEngine<D, 2, HALF>>;
+    case 4: return decode_partial_kernel<MatEngine<D, 4, HALF>>;
+    case 8: return decode_partial_kernel<MatEngine<D, 8, HALF>>;
+    default: return decode_partial_kernel<MatEngine<D, 16, HALF>>;
+  }
+}
+
 template <typename E, int D>
-DecodeFn pick_g(bool mat, bool quad, int G) {
+DecodeFn pick_g(bool mat, bool half_pages, bool quad, int G) {
   constexpr int kRow = D * E::kBytes;
   if constexpr (E::kBytes == 2) {
-    if (mat) {
-      switch (G) {
-        case 1: return decode_partial_kernel<MatEngine<D, 1>>;
-        case 2: return decode_partial_kernel<MatEngine<D, 2>>;
-        case 4: return decode_partial_kernel<MatEngine<D, 4>>;
-        default: break;
-      }
-      if (G == 16) return decode_partial_kernel<MatEngine<D, 16>>;
-      return decode_partial_kernel<MatEngine<D, 8>>;
-    }
+    if (mat) return half_pages ? pick_mat<D, true>(G) : pick_mat<D, false>(G);
   }
   if constexpr (kRow <= 512 && (E::kBytes == 4 || kRow == 512)) {
     if (quad) {
@@ -323,20 +325,23 @@ DecodeFn pick_g(bool mat, bool quad, int G) {
       }
     }
   }
-  switch (G) {
-    case 1: return decode_partial_kernel<RowEngine<E, D, 1>>;
-    case 2: return decode_partial_kernel<RowEngine<E, D, 2>>;
-    case 4: return decode_partial_kernel<RowEngine<E, D, 4>>;
-    default: return decode_partial_kernel<RowEngine<E, D, 8>>;
+  if constexpr (E::kBytes == 4) {
+    switch (G) {
+      case 1: return decode_partial_kernel<RowEngine<E, D, 1>>;
+      case 2: return decode_partial_kernel<RowEngine<E, D, 2>>;
+      case 4: return decode_partial_kernel<RowEngine<E, D, 4>>;
+      default: return decode_partial_kernel<RowEngine<E, D, 8>>;
+    }
   }
+  return nullptr;      // not reached: every bf16 shape has been dispatched above
 }
 
 template <typename E>
-DecodeFn pick_d(int D, bool mat, bool quad, int G) {
+DecodeFn pick_d(int D, bool mat, bool half_pages, bool quad, int G) {
   switch (D) {
-    case 64: return pick_g<E, 64>(mat, quad, G);
-    case 128: return pick_g<E, 128>(mat, quad, G);
-    default: return pick_g<E, 256>(mat, quad, G);
+    case 64: return pick_g<E, 64>(mat, half_pages, quad, G);
+    case 128: return pick_g<E, 128>(mat, half_pages, quad, G);
+    default: return pick_g<E, 256>(mat, half_pages, quad, G);
   }
 }
 
@@ -373,7 +378,7 @@ struct Geometry {
   const jenga::Kind* kind;
   int G;
   bool quad;             // 16-token pages, vector-ALU engine
-  bool mat;              // bf16, pages of 16 tokens or more, matrix-core engine
+  bool mat;              // bf16, matrix-core engine
   int tile_log2;
   int chunk_tiles;       // 0: automatic
   int min_chunk_tiles;
@@ -397,18 +402,17 @@ int decode_geometry(const jenga_pool* pool, int32_t kind, int32_t n_q_heads, int
   if (n_q_heads % k.desc.n_kv_heads != 0) return JENGA_ERR_INVALID;
   const int G = n_q_heads / k.desc.n_kv_heads;
   if (G != 1 && G != 2 && G != 4 && G != 8 && G != 16) return JENGA_ERR_UNSUPPORTED;
-  if (G == 16 && !(k.desc.dtype == JENGA_BF16 && k.t_log2 >= 4)) return JENGA_ERR_UNSUPPORTED;
+  if (G == 16 && k.desc.dtype != JENGA_BF16) return JENGA_ERR_UNSUPPORTED;
   const int row = k.desc.head_dim * k.elem_bytes;
   const int T = k.desc.tokens_per_page;
   out->kind = &k;
   out->G = G;
-  // bf16 K/V in pages of 16 tokens or more goes to the matrix-core engine, except 16-token pages of
-  // 256-element rows with up to 4 query heads per KV head, where the quad engine measures 0.7 %
-  // faster; fp32 K/V in 16-token pages goes to the quad engine up to 4 heads per KV head.
-  // Everything else takes the general engine.
+  // bf16 K/V goes to the matrix-core engine, except 16-token pages of 256-element rows with up to 4
+  // query heads per KV head, where the quad engine measures 0.7 % faster; fp32 K/V in 16-token
+  // pages goes to the quad engine up to 4 heads per KV head, other fp32 K/V to the general engine.
   out->quad = k.t_log2 == 4 && G <= 4 && row <= 512 &&
               (k.desc.dtype == JENGA_F32 || row == 512);
-  out->mat = k.t_log2 >= 4 && k.desc.dtype == JENGA_BF16 && !out->quad;
+  out->mat = k.desc.dtype == JENGA_BF16 && !out->quad;
   const bool paged16 = out->mat || out->quad;      // tiles of 8 KiB K + 8 KiB V in whole pages
   const int tile_tokens = paged16 ? (8 / (row / 64)) * 16 : 8 * (kWave / (row / 16));
   out->tile_log2 = 0;
@@ -418,8 +422,10 @@ int decode_geometry(const jenga_pool* pool, int32_t kind, int32_t n_q_heads, int
   const int64_t max_tiles = (max_pages * T + tile_tokens - 1) / tile_tokens;
   const int64_t w_max = (max_tiles + kSegStartUnits) * k.desc.n_kv_heads * std::max(batch, 1);
   if (w_max > 0x3fffffff) return JENGA_ERR_UNSUPPORTED;
-  out->fn = k.desc.dtype == JENGA_F32 ? pick_d<F32>(k.desc.head_dim, out->mat, out->quad, G)
-                                      : pick_d<BF16>(k.desc.head_dim, out->mat, out->quad, G);
+  const bool half_pages = k.t_log2 == 3;
+  out->fn = k.desc.dtype == JENGA_F32 ? pick_d<F32>(k.desc.head_dim, out->mat, half_pages, out->quad, G)
+                                      : pick_d<BF16>(k.desc.head_dim, out->mat, half_pages, out->quad, G);
+  if (out->fn == nullptr) return JENGA_ERR_UNSUPPORTED;
   const int64_t tile_bytes = int64_t(tile_tokens) * row * 2;
   out->min_chunk_tiles = int(std::max<int64_t>(1, (64 * 1024) / tile_bytes));
   if (pages_per_split > 0) {
