@@ -11,8 +11,9 @@ namespace {
 // TPL = 64 / LPT consecutive tokens (1 KiB, contiguous in the page).  Every partial dot
 // product is summed over LPT lanes, so this engine spends several times more vector-ALU
 // work per byte than the other two; it covers what they are not built for (fp32 K/V in pages
-// other than 16 tokens, with 8 query heads per KV head, or with 1 KiB rows).  Each group of LPT lanes runs
-// its own online softmax over the tokens it sees; the groups are merged once at the end.
+// other than 16 tokens, with 8 query heads per KV head, or with 1 KiB rows).  Each group of
+// LPT lanes runs its own online softmax over the tokens it sees; the groups are merged once at
+// the end.
 template <typename E_, int D_, int G_>
 struct RowEngine {
   using E = E_;
