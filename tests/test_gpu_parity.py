@@ -127,7 +127,7 @@ def test_all_built_shapes_full_attention(dtype, D, G):
     (64, "bf16", 128, 4, 0), (64, "f32", 128, 2, 70), (128, "bf16", 64, 2, 0), (128, "f32", 256, 1, 300),
     (8, "f32", 256, 2, 9)])
 def test_other_page_sizes(T, dtype, D, G, window):
-    """Pages of 8, 32, 64 and 128 tokens go through the general (row) engine."""
+    """Pages of 8, 32, 64 and 128 tokens: the matrix-core engine for bf16, the general (row) engine for fp32."""
     print(f"[case] T={T} {dtype} D={D} G={G} W={window}", flush=True)
     cfg = custom_cfg(dtype, D, 2 * G, 2, WINDOW if window else FULL, window=window, hi=900, T=T)
     for pps in (0, 2):
