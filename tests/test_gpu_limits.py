@@ -65,6 +65,20 @@ def test_one_very_long_request_among_short_ones(dtype, D, G, window):
     r.close()
 
 
+@pytest.mark.parametrize("T,D,G", [(8, 128, 4), (8, 64, 16), (128, 256, 2), (32, 128, 8)])
+def test_long_request_other_page_sizes(T, D, G):
+    """Thousands of pages per request with 8-token pages (the page-id registers are refilled every
+    64 pages, several times per partition), a few hundred with 128-token pages."""
+    print(f"[case] long request T={T} D={D} G={G}", flush=True)
+    cfg = custom_cfg("bf16", D, 2 * G, 2, FULL, batch=3, n_layers=1, T=T)
+    r = _runner(cfg, 19, ctx=np.array([30001, 7, 12345]))
+    prepare(r)
+    r.device_step()
+    check_against_oracle(r, cfg.name)
+    check_append_landed(r)
+    r.close()
+
+
 def test_lengths_above_max_seq_len_are_clamped():
     """A length above max_seq_len is treated as max_seq_len: the result is that of the clamped
     length, and nothing past the table's width is read."""
