@@ -22,7 +22,7 @@ def draw_case(seed):
     window = int(rng.choice([0, 0, rng.integers(1, 400)]))
     pps = int(rng.choice([0, 0, 1, 2, 3, 5, 8, 40]))
     batch = int(rng.integers(1, 9))
-    hi = int(rng.choice([40, 300, 1200]))
+    hi = int(rng.choice([40, 300, 1200, 6000]))     # up to 750 pages of 8 tokens: several refills of the page-id registers
     ctx = rng.integers(0, hi, size=batch)
     # lengths that sit on page and tile boundaries are the interesting ones: plant a few
     for i in range(batch):
