@@ -65,13 +65,14 @@ def test_one_very_long_request_among_short_ones(dtype, D, G, window):
     r.close()
 
 
-@pytest.mark.parametrize("T,D,G", [(8, 128, 4), (8, 64, 16), (128, 256, 2), (32, 128, 8)])
-def test_long_request_other_page_sizes(T, D, G):
-    """Thousands of pages per request with 8-token pages (the page-id registers are refilled every
-    64 pages, several times per partition), a few hundred with 128-token pages."""
-    print(f"[case] long request T={T} D={D} G={G}", flush=True)
+@pytest.mark.parametrize("T,D,G,pps", [(8, 128, 4, 0), (8, 64, 16, 700), (128, 256, 2, 0), (32, 128, 8, 300),
+                                         (16, 128, 4, 1000), (16, 256, 2, 500), (16, 64, 8, 4000)])
+def test_long_request_other_page_sizes(T, D, G, pps):
+    """Thousands of pages per request; with large partitions one wavefront walks through many runs
+    of 64 pages, so its page-id registers are refilled again and again."""
+    print(f"[case] long request T={T} D={D} G={G} pps={pps}", flush=True)
     cfg = custom_cfg("bf16", D, 2 * G, 2, FULL, batch=3, n_layers=1, T=T)
-    r = _runner(cfg, 19, ctx=np.array([30001, 7, 12345]))
+    r = _runner(cfg, 19, ctx=np.array([30001, 7, 12345]), pages_per_split=pps)
     prepare(r)
     r.device_step()
     check_against_oracle(r, cfg.name)

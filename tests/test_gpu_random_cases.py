@@ -20,7 +20,8 @@ def draw_case(seed):
     G = int(rng.choice(groups))
     Hkv = int(rng.choice([1, 2, 3]))
     window = int(rng.choice([0, 0, rng.integers(1, 400)]))
-    pps = int(rng.choice([0, 0, 1, 2, 3, 5, 8, 40]))
+    # partitions of 150 and 1000 pages make one wavefront walk through several runs of 64 pages
+    pps = int(rng.choice([0, 0, 1, 2, 3, 5, 8, 40, 150, 1000]))
     batch = int(rng.integers(1, 9))
     hi = int(rng.choice([40, 300, 1200, 6000]))     # up to 750 pages of 8 tokens: several refills of the page-id registers
     ctx = rng.integers(0, hi, size=batch)
