@@ -263,7 +263,7 @@ int jenga_decode_num_partitions(const jenga_pool* pool, int32_t kind, int32_t n_
                                 int32_t pages_per_split);
 /* Bytes of split-K workspace jenga_paged_decode needs for these arguments (> 0), or a
  * negative status: one (max, sum, accumulator) record per query head for each of
- * (partitions + batch * n_kv_heads) slots. */
+ * (partitions + batch * n_kv_heads) slots, plus 8 bytes per (request, KV head). */
 int64_t jenga_decode_workspace_bytes(const jenga_pool* pool, int32_t kind, int32_t n_q_heads,
                                      int32_t batch, int32_t max_seq_len, int32_t window,
                                      int32_t pages_per_split);

@@ -43,6 +43,7 @@ struct DecodeParams {
   const void* v_new;
   float* ws_acc;              // [slot][G][D]
   float* ws_ml;               // [slot][G][2]  (running max, running sum)
+  int32_t* ws_meta;           // [segment][2]  first and last chunk that hold tiles of the segment
 };
 
 // Visible pages [p_lo, p_hi) and first visible token of a request of length L.

@@ -78,7 +78,11 @@ __global__ __launch_bounds__(kWave) void decode_partial_kernel(const DecodeParam
     const int tile0 = max(x - seg0 - kSegStartUnits, 0);
     const int n_tiles = xe - seg0 - kSegStartUnits - tile0;
     if (n_tiles > 0) {
-      const int64_t slot = int64_t(b) * p.n_kv_heads + kvh + blockIdx.x;
+      const int64_t seg = int64_t(b) * p.n_kv_heads + kvh;
+      const int64_t slot = seg + blockIdx.x;
+      // the wavefront that holds a segment's first tile tells the reduction where its records are
+      if (tile0 == 0 && lane == 0)
+        *reinterpret_cast<int2*>(p.ws_meta + seg * 2) = make_int2(int(blockIdx.x), (seg0 + units_b - 1) / C);
       // fused append: the chunk that holds the tile of the newest token (position L - 1) writes it
       int append_tile = -1;
       if (p.k_new != nullptr) {
@@ -96,71 +100,56 @@ __global__ __launch_bounds__(kWave) void decode_partial_kernel(const DecodeParam
 
 // One block (one wavefront) per (request, query head): merges the records of its segment,
 //   m* = max m_i,  out = sum_i acc_i 2^(m_i - m*) / sum_i l_i 2^(m_i - m*).
-// Thread i < D/4 owns output elements [4i, 4i+4); all 64 lanes take part in the scan.
-template <int D>
-__global__ __launch_bounds__(kWave) void splitk_reduce_kernel(
-    const float* __restrict__ ws_acc, const float* __restrict__ ws_ml,
-    const int32_t* __restrict__ seq_lens, int32_t batch, int32_t max_seq_len, int32_t window,
-    int32_t t_log2, int32_t tile_log2, int32_t chunk_tiles, int32_t min_chunk_tiles, int32_t n_part,
-    int32_t n_kv_heads, int32_t n_q_heads, float* __restrict__ out) {
+// D/4 lanes cover an output row (4 elements each), so the wavefront holds 256/D lane groups;
+// group i takes every (256/D)-th record, eight records are in flight per step over all groups
+// (all loads issued before any is used), and the groups are merged at the end.  Where the
+// records are comes from the (first chunk, last chunk) pair the partial kernel left per segment.
+// NW wavefronts per block share a segment's records the same way when a few long segments have
+// many records each (a single request of 100 k tokens has 128 per KV head), and meet in LDS.
+template <int D, int NW>
+__global__ __launch_bounds__(kWave * NW) void splitk_reduce_kernel(
+    const float* __restrict__ ws_acc, const float* __restrict__ ws_ml, const int32_t* __restrict__ ws_meta,
+    const int32_t* __restrict__ seq_lens, int32_t n_kv_heads, int32_t n_q_heads, float* __restrict__ out) {
+  constexpr int LPR = D / 4;              // lanes per output row
+  constexpr int NG = kWave / LPR;         // lane groups: 4, 2 or 1
+  constexpr int R = 8 / NG;               // records per group and step
   const int hq = blockIdx.x;
   const int b = blockIdx.y;
-  const int lane = threadIdx.x;
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = threadIdx.x / kWave;
+  const int gi = lane / LPR, li = lane % LPR;
   const int G = n_q_heads / n_kv_heads;
-  // prefix of units * heads up to request b, and W
-  int run = 0, start_b = 0, units_b = 0;
-  for (int c0 = 0; c0 < batch; c0 += kWave) {
-    const int i = c0 + lane;
-    const int Li = i < batch ? min(seq_lens[i], max_seq_len) : 0;
-    const int n = units_of(Li, window, t_log2, tile_log2);
-    int incl = n * n_kv_heads;
-#pragma unroll
-    for (int off = 1; off < kWave; off <<= 1) {
-      const int up = __shfl_up(incl, off);
-      if (lane >= off) incl += up;
-    }
-    if (b >= c0 && b < c0 + kWave) {
-      units_b = __builtin_amdgcn_readlane(n, b - c0);
-      start_b = run + __builtin_amdgcn_readlane(incl, b - c0) - units_b * n_kv_heads;
-    }
-    run += __builtin_amdgcn_readlane(incl, kWave - 1);
-  }
-  const bool owner = lane < D / 4;
-  float4* dst = reinterpret_cast<float4*>(out + (int64_t(b) * n_q_heads + hq) * D) + lane;
-  if (units_b == 0) {
-    if (owner) *dst = make_float4(0.f, 0.f, 0.f, 0.f);
-    return;
-  }
-  const int C = chunk_of(chunk_tiles, min_chunk_tiles, run, n_part);
   const int kvh = hq / G;
   const int g = hq - kvh * G;
-  const int S = start_b + kvh * units_b + kSegStartUnits;   // flat position of the segment's first tile
-  const int c_lo = S / C;
-  const int c_hi = (S + (units_b - kSegStartUnits) - 1) / C;
+  float4* dst = reinterpret_cast<float4*>(out + (int64_t(b) * n_q_heads + hq) * D) + li;
+  if (seq_lens[b] <= 0) {                 // no visible token, no record (the whole block leaves)
+    if (gi == 0 && wave == 0) *dst = make_float4(0.f, 0.f, 0.f, 0.f);
+    return;
+  }
   const int64_t seg = int64_t(b) * n_kv_heads + kvh;
-  // Four records at a time, all their loads issued before any is used (a segment rarely has
-  // more than four); the running maximum is carried from one group to the next.
+  const int2 span = *reinterpret_cast<const int2*>(ws_meta + seg * 2);
+  const int c_lo = span.x, c_hi = span.y;
   float m_star = kNegBig, l_star = 0.f;
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-  for (int c0 = c_lo; c0 <= c_hi; c0 += 4) {
-    float2 ml[4];
-    float4 a[4];
+  for (int c0 = c_lo + wave * (R * NG); c0 <= c_hi; c0 += R * NG * NW) {
+    float2 ml[R];
+    float4 a[R];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int64_t rec = (seg + min(c0 + i, c_hi)) * G + g;
+    for (int i = 0; i < R; ++i) {
+      const int64_t rec = (seg + min(c0 + i * NG + gi, c_hi)) * G + g;
       ml[i] = *reinterpret_cast<const float2*>(ws_ml + rec * 2);
-      a[i] = owner ? *(reinterpret_cast<const float4*>(ws_acc + rec * D) + lane) : make_float4(0.f, 0.f, 0.f, 0.f);
+      a[i] = *(reinterpret_cast<const float4*>(ws_acc + rec * D) + li);
     }
     float m_new = m_star;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-      if (c0 + i <= c_hi) m_new = fmaxf(m_new, ml[i].x);
+    for (int i = 0; i < R; ++i)
+      if (c0 + i * NG + gi <= c_hi) m_new = fmaxf(m_new, ml[i].x);
     const float keep = __builtin_amdgcn_exp2f(m_star - m_new);
     l_star *= keep;
     acc.x *= keep; acc.y *= keep; acc.z *= keep; acc.w *= keep;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      if (c0 + i > c_hi) continue;
+    for (int i = 0; i < R; ++i) {
+      if (c0 + i * NG + gi > c_hi) continue;
       const float w = __builtin_amdgcn_exp2f(ml[i].x - m_new);
       l_star = fmaf(ml[i].y, w, l_star);
       acc.x = fmaf(a[i].x, w, acc.x); acc.y = fmaf(a[i].y, w, acc.y);
@@ -168,8 +157,46 @@ __global__ __launch_bounds__(kWave) void splitk_reduce_kernel(
     }
     m_star = m_new;
   }
+  // merge the lane groups (a group that saw no record still has m = -big, l = 0, acc = 0)
+#pragma unroll
+  for (int off = LPR; off < kWave; off <<= 1) {
+    const float m_o = __shfl_xor(m_star, off);
+    const float l_o = __shfl_xor(l_star, off);
+    const float m_new = fmaxf(m_star, m_o);
+    const float wa = __builtin_amdgcn_exp2f(m_star - m_new);
+    const float wb = __builtin_amdgcn_exp2f(m_o - m_new);
+    l_star = l_star * wa + l_o * wb;
+    acc.x = acc.x * wa + __shfl_xor(acc.x, off) * wb;
+    acc.y = acc.y * wa + __shfl_xor(acc.y, off) * wb;
+    acc.z = acc.z * wa + __shfl_xor(acc.z, off) * wb;
+    acc.w = acc.w * wa + __shfl_xor(acc.w, off) * wb;
+    m_star = m_new;
+  }
+  if constexpr (NW > 1) {
+    __shared__ float4 s_acc[NW][LPR];
+    __shared__ float2 s_ml[NW];
+    if (gi == 0) {
+      s_acc[wave][li] = acc;
+      if (li == 0) s_ml[wave] = make_float2(m_star, l_star);
+    }
+    __syncthreads();
+    if (wave != 0) return;
+    m_star = kNegBig;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) m_star = fmaxf(m_star, s_ml[w].x);
+    l_star = 0.f;
+    acc = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+      const float f = __builtin_amdgcn_exp2f(s_ml[w].x - m_star);
+      const float4 a = s_acc[w][li];
+      l_star = fmaf(s_ml[w].y, f, l_star);
+      acc.x = fmaf(a.x, f, acc.x); acc.y = fmaf(a.y, f, acc.y);
+      acc.z = fmaf(a.z, f, acc.z); acc.w = fmaf(a.w, f, acc.w);
+    }
+  }
   const float inv = l_star > 0.f ? 1.0f / l_star : 0.f;
-  if (owner) *dst = make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv);
+  if (gi == 0) *dst = make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv);
 }
 
 // One thread per 16 bytes of the new K and V rows.
@@ -379,7 +406,6 @@ struct Geometry {
   int G;
   bool quad;             // 16-token pages, vector-ALU engine
   bool mat;              // bf16, matrix-core engine
-  int tile_log2;
   int chunk_tiles;       // 0: automatic
   int min_chunk_tiles;
   int n_part_bound;      // partitions the workspace must have room for
@@ -415,8 +441,6 @@ int decode_geometry(const jenga_pool* pool, int32_t kind, int32_t n_q_heads, int
   out->mat = k.desc.dtype == JENGA_BF16 && !out->quad;
   const bool paged16 = out->mat || out->quad;      // tiles of 8 KiB K + 8 KiB V in whole pages
   const int tile_tokens = paged16 ? (8 / (row / 64)) * 16 : 8 * (kWave / (row / 16));
-  out->tile_log2 = 0;
-  while ((1 << out->tile_log2) < tile_tokens) ++out->tile_log2;
   int64_t max_pages = (int64_t(max_seq_len) + T - 1) / T;
   if (window > 0) max_pages = std::min<int64_t>(max_pages, window / T + 2);
   const int64_t max_tiles = (max_pages * T + tile_tokens - 1) / tile_tokens;
@@ -445,18 +469,24 @@ int launch_partitions(const Geometry& g) {
   return g.chunk_tiles > 0 ? g.n_part_bound : resident_partitions(g.fn);
 }
 
+// Workspace layout: accumulators [slot][G][D], (max, sum) pairs [slot][G][2], then the
+// (first chunk, last chunk) pair of every (request, KV head) segment.
+int64_t segments_of(const Geometry& g) { return g.slots - g.n_part_bound; }
+
 int64_t workspace_bytes_for(const Geometry& g) {
-  return g.slots * g.G * (g.kind->desc.head_dim + 2) * 4;
+  return g.slots * g.G * (g.kind->desc.head_dim + 2) * 4 + segments_of(g) * 8;
 }
 
 int hip_status() { return hipGetLastError() == hipSuccess ? JENGA_OK : JENGA_ERR_HIP; }
 
-int split_ws(const Geometry& g, void* workspace, int64_t workspace_bytes, float** acc, float** ml) {
+int split_ws(const Geometry& g, void* workspace, int64_t workspace_bytes, float** acc, float** ml,
+             int32_t** meta) {
   if (!workspace) return JENGA_ERR_INVALID;
   if (!aligned16(workspace)) return JENGA_ERR_ALIGN;
   if (workspace_bytes < workspace_bytes_for(g)) return JENGA_ERR_WORKSPACE;
   *acc = static_cast<float*>(workspace);
   *ml = *acc + g.slots * g.G * g.kind->desc.head_dim;
+  *meta = reinterpret_cast<int32_t*>(*ml + g.slots * g.G * 2);
   return JENGA_OK;
 }
 
@@ -549,7 +579,8 @@ int jenga_paged_decode_partial(const jenga_pool* pool, int32_t kind, int32_t lay
   if (k_new && k.desc.type != JENGA_FULL && k.desc.type != JENGA_WINDOW) return JENGA_ERR_INVALID;
   if (k_new && (!aligned16(k_new) || !aligned16(v_new))) return JENGA_ERR_ALIGN;
   float *acc = nullptr, *ml = nullptr;
-  rc = split_ws(g, workspace, workspace_bytes, &acc, &ml);
+  int32_t* meta = nullptr;
+  rc = split_ws(g, workspace, workspace_bytes, &acc, &ml, &meta);
   if (rc != JENGA_OK) return rc;
   if (batch == 0) return JENGA_OK;
 
@@ -577,6 +608,7 @@ int jenga_paged_decode_partial(const jenga_pool* pool, int32_t kind, int32_t lay
   p.v_new = v_new;
   p.ws_acc = acc;
   p.ws_ml = ml;
+  p.ws_meta = meta;
   const int n_part = launch_partitions(g);
   hipLaunchKernelGGL(g.fn, dim3(unsigned(n_part)), dim3(kWave), 0, static_cast<hipStream_t>(stream), p);
   return hip_status();
@@ -593,16 +625,22 @@ int jenga_splitk_reduce(const jenga_pool* pool, int32_t kind, int32_t n_q_heads,
   if (!seq_lens || !out) return JENGA_ERR_INVALID;
   if (!aligned16(out)) return JENGA_ERR_ALIGN;
   float *acc = nullptr, *ml = nullptr;
-  rc = split_ws(g, const_cast<void*>(workspace), workspace_bytes, &acc, &ml);
+  int32_t* meta = nullptr;
+  rc = split_ws(g, const_cast<void*>(workspace), workspace_bytes, &acc, &ml, &meta);
   if (rc != JENGA_OK) return rc;
   if (batch == 0) return JENGA_OK;
-  const int n_part = launch_partitions(g);
   const dim3 grid(static_cast<unsigned>(n_q_heads), static_cast<unsigned>(batch));
   hipStream_t st = static_cast<hipStream_t>(stream);
-#define JENGA_LAUNCH_REDUCE(DIM)                                                                   \
-  hipLaunchKernelGGL((splitk_reduce_kernel<DIM>), grid, dim3(kWave), 0, st, acc, ml, seq_lens,    \
-                     batch, max_seq_len, window, k.t_log2, g.tile_log2, g.chunk_tiles,             \
-                     g.min_chunk_tiles, n_part, k.desc.n_kv_heads, n_q_heads, out)
+  // Four wavefronts per (request, query head) when the segments are few enough to have more than
+  // about eight records each.
+  const bool wide = launch_partitions(g) >= 8 * segments_of(g);
+#define JENGA_LAUNCH_REDUCE(DIM)                                                                       \
+  if (wide)                                                                                            \
+    hipLaunchKernelGGL((splitk_reduce_kernel<DIM, 4>), grid, dim3(4 * kWave), 0, st, acc, ml, meta,   \
+                       seq_lens, k.desc.n_kv_heads, n_q_heads, out);                                   \
+  else                                                                                                 \
+    hipLaunchKernelGGL((splitk_reduce_kernel<DIM, 1>), grid, dim3(kWave), 0, st, acc, ml, meta,       \
+                       seq_lens, k.desc.n_kv_heads, n_q_heads, out)
   switch (k.desc.head_dim) {
     case 64: JENGA_LAUNCH_REDUCE(64); break;
     case 128: JENGA_LAUNCH_REDUCE(128); break;

@@ -212,12 +212,12 @@ def test_partition_geometry_and_workspace_queries():
     # automatic: a fixed bound, independent of the lengths
     n = lib.decode_num_partitions(0, 16, 64, 8193)
     assert n == 8192
-    assert lib.decode_workspace_bytes(0, 16, 64, 8193) == (n + 64 * 8) * 2 * (256 + 2) * 4
+    assert lib.decode_workspace_bytes(0, 16, 64, 8193) == (n + 64 * 8) * 2 * (256 + 2) * 4 + 64 * 8 * 8
     # explicit partition size: 513 pages of 16 tokens, one page per tile (plus 3 start-up units
     # per request and KV head), 32 units per partition
     n32 = lib.decode_num_partitions(0, 16, 64, 8193, pages_per_split=32)
     assert n32 == -(-((513 + 3) * 8 * 64) // 32)
-    assert lib.decode_workspace_bytes(0, 16, 64, 8193, pages_per_split=32) == (n32 + 512) * 2 * 258 * 4
+    assert lib.decode_workspace_bytes(0, 16, 64, 8193, pages_per_split=32) == (n32 + 512) * 2 * 258 * 4 + 512 * 8
     # a window bounds the visible pages
     nw = lib.decode_num_partitions(1, 16, 64, 8193, window=4096, pages_per_split=32)
     assert nw == -(-((4096 // 16 + 2 + 3) * 8 * 64) // 32)
