@@ -188,30 +188,41 @@ struct MatEngine {
       k_entered(1);
     }
 
+    // Fused append: the new token's rows and its page's table entry are requested now, so that the
+    // tile that takes them in (often the last of the segment) does not wait for them.
+    u32x4 k_app[KCH], v_app = u32x4{0, 0, 0, 0};
+    int raw_new = -1;
+    const int rel = (L - 1) - (p_lo << p.t_log2);                // the new token, counted from the first visible page
+    const int r_new = (rel >> 4) - blk0;                         // its block, relative to the chunk
+    const int row_new = rel & 15;                                // its row in the block
+    const int page_new = t8 ? 2 * r_new + (row_new >> 3) : (off0 + r_new) >> sh;
+#pragma unroll
+    for (int c = 0; c < KCH; ++c) k_app[c] = u32x4{0, 0, 0, 0};
+    if (append_tile >= 0) {
+      const char* kn = static_cast<const char*>(p.k_new) + (int64_t(b) * p.n_kv_heads + kvh) * ROW;
+      const char* vn = static_cast<const char*>(p.v_new) + (int64_t(b) * p.n_kv_heads + kvh) * ROW;
+#pragma unroll
+      for (int c = 0; c < KCH; ++c) k_app[c] = *reinterpret_cast<const u32x4*>(kn + j * 16 + c * 64);
+      v_app = *reinterpret_cast<const u32x4*>(vn + (lane % LPT) * 16);
+      raw_new = ids.row[page_new];
+    }
+
     auto step = [&](int tile, u32x4* kbuf, u32x4* vbuf) {
 
       // fused append: rows of the token at L - 1 come from k_new / v_new and are stored into the page
       if (tile == append_tile) {
-        const char* kn = static_cast<const char*>(p.k_new) + (int64_t(b) * p.n_kv_heads + kvh) * ROW;
-        const char* vn = static_cast<const char*>(p.v_new) + (int64_t(b) * p.n_kv_heads + kvh) * ROW;
-        const int rel = (L - 1) - (p_lo << p.t_log2);            // the new token, counted from the first visible page
-        const int r_new = (rel >> 4) - blk0;                     // its block, relative to the chunk
-        const int row_new = rel & 15;                            // its row in the block
         const int pp_new = r_new - tile * PPT;
-        const int page_rel = t8 ? 2 * r_new + (row_new >> 3) : (off0 + r_new) >> sh;
         char* dst = const_cast<char*>(half_base(r_new, row_new >> 3)) + (row_new & 7) * ROW;
-        const bool store = ids.writable(page_rel);
+        const bool store = raw_new >= 0 && raw_new <= p.max_page_id;
         if (n == row_new) {
 #pragma unroll
           for (int c = 0; c < KCH; ++c) {
-            const u32x4 k_app = *reinterpret_cast<const u32x4*>(kn + j * 16 + c * 64);
-            if (store) *reinterpret_cast<u32x4*>(dst + j * 16 + c * 64) = k_app;
+            if (store) *reinterpret_cast<u32x4*>(dst + j * 16 + c * 64) = k_app[c];
 #pragma unroll
             for (int pp = 0; pp < PPT; ++pp)
-              if (pp == pp_new) kbuf[pp * KCH + c] = k_app;
+              if (pp == pp_new) kbuf[pp * KCH + c] = k_app[c];
           }
         }
-        const u32x4 v_app = *reinterpret_cast<const u32x4*>(vn + (lane % LPT) * 16);
         bool mine = false;
 #pragma unroll
         for (int i = 0; i < NLD; ++i) {
