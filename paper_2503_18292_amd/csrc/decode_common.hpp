@@ -28,6 +28,7 @@ struct DecodeParams {
   int32_t t_log2;
   int32_t n_kv_heads;
   int32_t n_q_heads;
+  int32_t group;           // query heads per KV head
   int32_t max_page_id;        // ids read from the block table are clamped to [0, max_page_id]
   const void* q;
   const int32_t* block_table;

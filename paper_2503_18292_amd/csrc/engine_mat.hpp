@@ -12,7 +12,10 @@ namespace {
 // with 8 heads on every K/V byte those can no longer keep up with HBM (the quad engine would
 // need about 70 vector instructions per KiB), and with fewer heads the loads still issue
 // earlier and more evenly when so little else competes for the issue slots.  The G heads are
-// padded to the 16 rows / columns of the instructions.  Operand layouts (lane l, n = l % 16,
+// padded to the 16 rows / columns of the instructions, so any number from 1 to 16 can be served:
+// G_ = 0 is a build that takes it at run time (3, 5, 6, 7 ... heads per KV head), the powers of
+// two have builds of their own (1 % faster: the record stores and query loads are resolved at
+// compile time).  Operand layouts (lane l, n = l % 16,
 // j = l / 16), checked on the device: A holds row n and B holds column n, each with
 // consecutive k (8j .. 8j+7 for 16x16x32, 4j .. 4j+3 for 16x16x16); the result holds column n,
 // rows 4j .. 4j+3.
@@ -36,7 +39,8 @@ namespace {
 template <int D_, int G_, bool HALF_>
 struct MatEngine {
   using E = BF16;
-  static constexpr int D = D_, G = G_;
+  static constexpr int D = D_;
+  static_assert(G_ >= 0 && G_ <= 16, "heads are padded to 16");
   static constexpr int T = 16;                 // tokens per block; a page holds 1/2, 1, 2, 4 or 8 blocks
   static constexpr int ROW = D * 2;            // bytes per token row
   static constexpr int KCH = ROW / 64;         // k-steps of the score product == 1 KiB loads per page
@@ -49,7 +53,6 @@ struct MatEngine {
   static constexpr int kTileLog2 = PPT == 1 ? 4 : PPT == 2 ? 5 : 6;
   static constexpr int kLdsFloats = PPT * T * LROW / 4;
   static_assert(KCH == 2 || KCH == 4 || KCH == 8, "row size");
-  static_assert(G <= 16, "heads are padded to 16");
 
   typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
   typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
@@ -81,6 +84,7 @@ struct MatEngine {
     // (q & sub_mask) * 16.  An 8-token page is half a block: a block takes its rows 0..7 from one
     // page and its rows 8..15 from the next.
     constexpr bool t8 = HALF_;
+    const int G = G_ ? G_ : p.group;                           // query heads per KV head, at most 16
     const int sh = t8 ? 0 : p.t_log2 - 4;
     const int sub_mask = (1 << sh) - 1;
     int lo_tok, p_lo, p_hi;

@@ -333,7 +333,8 @@ DecodeFn pick_mat(int G) {
     case 2: return decode_partial_kernel<MatEngine<D, 2, HALF>>;
     case 4: return decode_partial_kernel<MatEngine<D, 4, HALF>>;
     case 8: return decode_partial_kernel<MatEngine<D, 8, HALF>>;
-    default: return decode_partial_kernel<MatEngine<D, 16, HALF>>;
+    case 16: return decode_partial_kernel<MatEngine<D, 16, HALF>>;
+    default: return decode_partial_kernel<MatEngine<D, 0, HALF>>;     // any other count up to 16, at run time
   }
 }
 
@@ -427,8 +428,10 @@ int decode_geometry(const jenga_pool* pool, int32_t kind, int32_t n_q_heads, int
   if (batch > kMaxBatch) return JENGA_ERR_UNSUPPORTED;
   if (n_q_heads % k.desc.n_kv_heads != 0) return JENGA_ERR_INVALID;
   const int G = n_q_heads / k.desc.n_kv_heads;
-  if (G != 1 && G != 2 && G != 4 && G != 8 && G != 16) return JENGA_ERR_UNSUPPORTED;
-  if (G == 16 && k.desc.dtype != JENGA_BF16) return JENGA_ERR_UNSUPPORTED;
+  // bf16 K/V: any number of query heads per KV head up to 16 (the matrix-core engine pads them to
+  // 16 anyway); fp32 K/V: the head counts the vector-ALU engines are built for
+  const bool pow2_le8 = G == 1 || G == 2 || G == 4 || G == 8;
+  if (k.desc.dtype == JENGA_BF16 ? G > 16 : !pow2_le8) return JENGA_ERR_UNSUPPORTED;
   const int row = k.desc.head_dim * k.elem_bytes;
   const int T = k.desc.tokens_per_page;
   out->kind = &k;
@@ -436,7 +439,7 @@ int decode_geometry(const jenga_pool* pool, int32_t kind, int32_t n_q_heads, int
   // bf16 K/V goes to the matrix-core engine, except 16-token pages of 256-element rows with up to 4
   // query heads per KV head, where the quad engine measures 0.7 % faster; fp32 K/V in 16-token
   // pages goes to the quad engine up to 4 heads per KV head, other fp32 K/V to the general engine.
-  out->quad = k.t_log2 == 4 && G <= 4 && row <= 512 &&
+  out->quad = k.t_log2 == 4 && (G == 1 || G == 2 || G == 4) && row <= 512 &&
               (k.desc.dtype == JENGA_F32 || row == 512);
   out->mat = k.desc.dtype == JENGA_BF16 && !out->quad;
   const bool paged16 = out->mat || out->quad;      // tiles of 8 KiB K + 8 KiB V in whole pages
@@ -593,6 +596,7 @@ int jenga_paged_decode_partial(const jenga_pool* pool, int32_t kind, int32_t lay
   p.t_log2 = k.t_log2;
   p.n_kv_heads = k.desc.n_kv_heads;
   p.n_q_heads = n_q_heads;
+  p.group = g.G;
   p.max_page_id = int32_t(pool->n_large * k.per_large - 1);
   p.q = q;
   p.block_table = block_table;

@@ -143,11 +143,13 @@ def test_other_page_sizes(T, dtype, D, G, window):
     (128, 8, 0, 0, 16), (128, 8, 200, 2, 16), (128, 16, 0, 6, 16), (64, 8, 70, 0, 16), (64, 4, 0, 4, 16),
     (256, 8, 0, 0, 16), (256, 16, 33, 1, 16), (128, 1, 0, 2, 16), (64, 16, 0, 0, 16),
     (128, 16, 100, 0, 64), (256, 2, 0, 1, 32), (64, 8, 0, 3, 128), (128, 4, 130, 0, 128), (256, 4, 0, 0, 64),
-    (128, 8, 0, 0, 8), (64, 16, 21, 3, 8), (256, 2, 0, 1, 8), (128, 4, 77, 0, 8)])
+    (128, 8, 0, 0, 8), (64, 16, 21, 3, 8), (256, 2, 0, 1, 8), (128, 4, 77, 0, 8),
+    (128, 3, 0, 0, 16), (128, 5, 90, 2, 16), (256, 3, 0, 0, 16), (64, 7, 0, 1, 32), (128, 6, 40, 0, 8),
+    (256, 12, 0, 3, 16), (64, 15, 0, 0, 16), (128, 9, 0, 0, 64)])
 def test_matrix_core_engine_shapes(D, G, window, pps, T):
     """bf16 K/V on the matrix-core engine, pages from 8 (half a 16-token block, odd page counts
-    included) to 128 tokens: ragged lengths from one token to many tiles, windows that start
-    inside a page, partitions that cut inside a page."""
+    included) to 128 tokens, any number of query heads per KV head up to 16: ragged lengths from
+    one token to many tiles, windows that start inside a page, partitions that cut inside a page."""
     print(f"[case] matrix-core D={D} G={G} W={window} pps={pps} T={T}", flush=True)
     cfg = custom_cfg("bf16", D, 2 * G, 2, WINDOW if window else FULL, window=window, batch=7, lo=0, hi=1300, T=T)
     r = _runner(cfg, 500 + D + G, pages_per_split=pps,

@@ -221,14 +221,22 @@ def test_partition_geometry_and_workspace_queries():
     # a window bounds the visible pages
     nw = lib.decode_num_partitions(1, 16, 64, 8193, window=4096, pages_per_split=32)
     assert nw == -(-((4096 // 16 + 2 + 3) * 8 * 64) // 32)
+    # bf16 K/V: any number of query heads per KV head up to 16
+    for hq in (24, 40, 56, 128):                          # G = 3, 5, 7, 16 over 8 KV heads
+        assert lib.decode_workspace_bytes(0, hq, 64, 8193) == (n + 64 * 8) * (hq // 8) * (256 + 2) * 4 + 64 * 8 * 8
     with pytest.raises(J.JengaError) as e:
-        lib.decode_workspace_bytes(0, 24, 64, 8193)      # 24 query heads over 8 KV heads: G = 3
+        lib.decode_workspace_bytes(0, 136, 64, 8193)      # G = 17
     assert e.value.status == -6
-    assert lib.decode_workspace_bytes(0, 128, 64, 8193) > 0    # G = 16: bf16 K/V in 16-token pages only
+    with pytest.raises(J.JengaError) as e:
+        lib.decode_workspace_bytes(0, 20, 64, 8193)       # not a multiple of the 8 KV heads
+    assert e.value.status == -1
+    # fp32 K/V: 1, 2, 4 or 8
     tiny_lib = make_library(configs.tiny(), 4)
-    with pytest.raises(J.JengaError) as e:
-        tiny_lib.decode_workspace_bytes(0, 32, 4, 256)       # fp32 K/V, 2 KV heads: G = 16
-    assert e.value.status == -6
+    for hq in (6, 32):                                    # 2 KV heads: G = 3, 16
+        with pytest.raises(J.JengaError) as e:
+            tiny_lib.decode_workspace_bytes(0, hq, 4, 256)
+        assert e.value.status == -6
+    assert tiny_lib.decode_workspace_bytes(0, 16, 4, 256) > 0
     with pytest.raises(J.JengaError) as e:
         lib.decode_workspace_bytes(0, 16, 5000, 8193)    # batch beyond the kernels' limit
     assert e.value.status == -6
