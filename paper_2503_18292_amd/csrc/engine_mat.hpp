@@ -180,17 +180,15 @@ struct MatEngine {
       }
     };
 
-    // K runs two tiles ahead in two register sets.  V has one: it goes to LDS as soon as its tile
-    // starts, and the next tile's V is requested right after.  (A second set with V a whole tile
-    // ahead measured 2 % slower on launches of 0.1-0.3 GB, up to 1.6 % faster on launches of
-    // several GB, and 0.3-0.5 % slower over whole steps of the three workloads that run here.)
-    u32x4 kb[2][NLD], vb[NLD];
-    load_k(0, kb[0]);
+    // One tile ahead, one register set each: a step first moves V(t) to LDS and issues the score
+    // products of K(t), which frees both sets, then requests K(t+1) and V(t+1) -- adjacent in
+    // memory -- back to back, with the rest of the step to arrive in.  Deeper pipelines measured
+    // slower: K two tiles ahead in a second register set by 1.5 % over whole steps (3 % on
+    // launches of 0.1-0.3 GB), a second V set by 0.3-0.5 %.  One wavefront per SIMD with 8-16 KiB in
+    // flight already covers the memory latency; more outstanding requests only lengthen the queues.
+    u32x4 kb[NLD], vb[NLD];
+    load_k(0, kb);
     load_v(0, vb);
-    if (n_tiles > 1) {
-      load_k(1, kb[1]);
-      k_entered(1);
-    }
 
     // Fused append: the new token's rows and its page's table entry are requested now, so that the
     // tile that takes them in (often the last of the segment) does not wait for them.
@@ -238,6 +236,21 @@ struct MatEngine {
         if (mine && store) *reinterpret_cast<u32x4*>(dst + p.v_offset + (lane % LPT) * 16) = v_app;
       }
 
+      const int tile_tok = tok0 + tile * PPT * T;
+      const bool clean = tile_tok >= lo_tok && tile_tok + PPT * T <= L;
+      if (!clean) {
+        // V rows outside the visible set may hold anything (even NaN): make them zero
+#pragma unroll
+        for (int i = 0; i < NLD; ++i) {
+          const int t = tile_tok + (i / KCH) * T + (i % KCH) * TPL + v_row;
+          if (t < lo_tok || t >= L) vbuf[i] = u32x4{0, 0, 0, 0};
+        }
+      }
+      // V rows into LDS, row-major
+#pragma unroll
+      for (int i = 0; i < NLD; ++i)
+        *reinterpret_cast<u32x4*>(v_lds + ((i / KCH) * T + (i % KCH) * TPL) * LROW + lds_wr) = vbuf[i];
+
       // scores: lane (n, j) gets head n, tokens 4j .. 4j+3 of each page
       f32x4 s[PPT];
 #pragma unroll
@@ -249,10 +262,12 @@ struct MatEngine {
                                                           s[pp], 0, 0, 0);
       }
 
-      if (tile + 2 < n_tiles) load_k(tile + 2, kbuf);
+      if (tile + 1 < n_tiles) {
+        load_k(tile + 1, kbuf);
+        load_v(tile + 1, vbuf);                            // the registers are free again
+        k_entered(tile + 1);
+      }
 
-      const int tile_tok = tok0 + tile * PPT * T;
-      const bool clean = tile_tok >= lo_tok && tile_tok + PPT * T <= L;
 #pragma unroll
       for (int pp = 0; pp < PPT; ++pp)
 #pragma unroll
@@ -265,23 +280,7 @@ struct MatEngine {
             const int t = tile_tok + pp * T + 4 * j + i;
             if (t < lo_tok || t >= L) s[pp][i] = kNegBig;
           }
-        // V rows outside the visible set may hold anything (even NaN): make them zero
-#pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-          const int t = tile_tok + (i / KCH) * T + (i % KCH) * TPL + v_row;
-          if (t < lo_tok || t >= L) vbuf[i] = u32x4{0, 0, 0, 0};
-        }
       }
-
-      // V rows into LDS, row-major
-#pragma unroll
-      for (int i = 0; i < NLD; ++i)
-        *reinterpret_cast<u32x4*>(v_lds + ((i / KCH) * T + (i % KCH) * TPL) * LROW + lds_wr) = vbuf[i];
-
-      if (tile + 1 < n_tiles) load_v(tile + 1, vbuf);      // the registers are free again
-      // Only now may the page-id registers move on: the refill that K's entry into a new run of 64
-      // pages triggers replaces the ids of the run before, which V(t+1) has just used.
-      if (tile + 2 < n_tiles) k_entered(tile + 2);
 
       // online softmax of head n
       float mx = s[0][0];
@@ -337,10 +336,7 @@ struct MatEngine {
       __builtin_amdgcn_wave_barrier();
     };
 
-    for (int tile = 0; tile < n_tiles; tile += 2) {
-      step(tile, kb[0], vb);
-      if (tile + 1 < n_tiles) step(tile + 1, kb[1], vb);
-    }
+    for (int tile = 0; tile < n_tiles; ++tile) step(tile, kb, vb);
 
     l = across_groups_sum(l);
     // one partial record: lane (n, j) holds element 16 * blk + n of heads 4j .. 4j+3

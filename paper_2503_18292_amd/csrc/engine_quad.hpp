@@ -89,18 +89,13 @@ struct QuadEngine {
       }
     };
 
-    // Software pipeline, two tiles deep: while tile t is computed, K(t+1), V(t+1) and (after the
-    // scores) K(t+2) are in flight, 16 to 32 KiB per wavefront.  Loads return in order, so
-    // waiting for the oldest tile leaves the younger ones outstanding.  (Issuing V(t) only at the
-    // start of tile t and K(t+1) after the scores measured the same with 2 query heads per KV
-    // head and 6 % slower with 4.)
-    u32x4 kb[2][NLD], vb[2][NLD];
-    load_pages(0, k_voff, 64, kb[0]);
+    // Software pipeline, one tile deep: V(t+1) is requested when tile t starts (into the second V
+    // set), K(t+1) as soon as the scores of tile t have freed the K registers; 8 to 16 KiB are in
+    // flight per wavefront.  (K two tiles ahead in a second register set measured the same on
+    // 512-byte rows with 2 query heads per KV head and needs 32 more registers.)
+    u32x4 kb[NLD], vb[2][NLD];
+    load_pages(0, k_voff, 64, kb);
     load_pages(0, v_voff, 1024, vb[0]);
-    if (n_tiles > 1) {
-      load_pages(1, k_voff, 64, kb[1]);
-      ids.k_stream_at(PPT);
-    }
 
     auto step = [&](int tile, u32x4* kbuf, u32x4* vbuf, u32x4* v_next) {
       if (tile + 1 < n_tiles) load_pages(tile + 1, v_voff, 1024, v_next);
@@ -157,9 +152,9 @@ struct QuadEngine {
           s[pp][g] = x * p.scale_log2;
         }
 
-      if (tile + 2 < n_tiles) {
-        load_pages(tile + 2, k_voff, 64, kbuf);
-        ids.k_stream_at((tile + 2) * PPT);
+      if (tile + 1 < n_tiles) {
+        load_pages(tile + 1, k_voff, 64, kbuf);
+        ids.k_stream_at((tile + 1) * PPT);
       }
 
       const int tile_tok = tok0 + tile * PPT * T;           // first token of the tile
@@ -221,8 +216,8 @@ struct QuadEngine {
     };
 
     for (int tile = 0; tile < n_tiles; tile += 2) {
-      step(tile, kb[0], vb[0], vb[1]);
-      if (tile + 1 < n_tiles) step(tile + 1, kb[1], vb[1], vb[0]);
+      step(tile, kb, vb[0], vb[1]);
+      if (tile + 1 < n_tiles) step(tile + 1, kb, vb[1], vb[0]);
     }
 
     // every quad of lanes carried the same l; the V lane groups share m, so they just add up
