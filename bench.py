@@ -27,10 +27,10 @@ HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
 # HBM traffic of one decode_partial launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
 # each scaled by what the same counter reads for a plain copy of known size (summaries and
 # commands: profiles/decode_kernels_*_hbm_traffic.md).  Default workload: fetched bytes are
-# 1.007 x the algorithmic K/V bytes, written bytes 3.70e6 per launch (split-K records and the
+# 1.004 x the algorithmic K/V bytes, written bytes 3.69e6 per launch (split-K records and the
 # appended rows).  Known for the workloads that were measured.
-MEASURED_TRAFFIC = {"gemma2_9b": {"fetch_over_algorithmic": 1.007, "write_bytes": 3.70e6},
-                    "long_5to1": {"fetch_over_algorithmic": 1.005, "write_bytes": 2.54e6}}
+MEASURED_TRAFFIC = {"gemma2_9b": {"fetch_over_algorithmic": 1.004, "write_bytes": 3.69e6},
+                    "long_5to1": {"fetch_over_algorithmic": 1.005, "write_bytes": 2.55e6}}
 
 
 def parse():

@@ -14,8 +14,8 @@
 // front end: the matrix-core engine (bf16 K/V, any page size: both products of a 16-token
 // block are small dense contractions and go through MFMA, which leaves the vector ALUs almost
 // idle and is what keeps 8 and 16 heads per KV head at the HBM rate), the quad engine
-// (16-token pages on the vector ALUs: fp32 K/V, and 256-element bf16 rows with few heads,
-// where it measures slightly faster), and the general row engine (the rest of fp32).
+// (fp32 K/V in 16-token pages, on the vector ALUs), and the general row engine (the rest of
+// fp32).
 //
 // The kernel view of the pool is the one of paper Sec. 4.2: a start pointer (pool base +
 // layer offset), a page stride (the kind's small-page size) and page ids (the kind's block
@@ -344,7 +344,7 @@ DecodeFn pick_g(bool mat, bool half_pages, bool quad, int G) {
   if constexpr (E::kBytes == 2) {
     if (mat) return half_pages ? pick_mat<D, true>(G) : pick_mat<D, false>(G);
   }
-  if constexpr (kRow <= 512 && (E::kBytes == 4 || kRow == 512)) {
+  if constexpr (kRow <= 512 && E::kBytes == 4) {
     if (quad) {
       switch (G) {
         case 1: return decode_partial_kernel<QuadEngine<E, D, 1>>;
@@ -436,11 +436,11 @@ int decode_geometry(const jenga_pool* pool, int32_t kind, int32_t n_q_heads, int
   const int T = k.desc.tokens_per_page;
   out->kind = &k;
   out->G = G;
-  // bf16 K/V goes to the matrix-core engine, except 16-token pages of 256-element rows with up to 4
-  // query heads per KV head, where the quad engine measures 0.7 % faster; fp32 K/V in 16-token
-  // pages goes to the quad engine up to 4 heads per KV head, other fp32 K/V to the general engine.
-  out->quad = k.t_log2 == 4 && (G == 1 || G == 2 || G == 4) && row <= 512 &&
-              (k.desc.dtype == JENGA_F32 || row == 512);
+  // bf16 K/V goes to the matrix-core engine (on 16-token pages of 256-element rows with 2 query
+  // heads per KV head the quad engine is within 0.3 % of it: 0.7 % ahead while K ran two tiles
+  // ahead, 0.25 % behind since it runs one); fp32 K/V in 16-token pages goes to the quad engine up
+  // to 4 heads per KV head, other fp32 K/V to the general engine.
+  out->quad = k.t_log2 == 4 && (G == 1 || G == 2 || G == 4) && row <= 512 && k.desc.dtype == JENGA_F32;
   out->mat = k.desc.dtype == JENGA_BF16 && !out->quad;
   const bool paged16 = out->mat || out->quad;      // tiles of 8 KiB K + 8 KiB V in whole pages
   const int tile_tokens = paged16 ? (8 / (row / 64)) * 16 : 8 * (kWave / (row / 16));
