@@ -442,8 +442,11 @@ int decode_geometry(const jenga_pool* pool, int32_t kind, int32_t n_q_heads, int
   // to 4 heads per KV head, other fp32 K/V to the general engine.
   out->quad = k.t_log2 == 4 && (G == 1 || G == 2 || G == 4) && row <= 512 && k.desc.dtype == JENGA_F32;
   out->mat = k.desc.dtype == JENGA_BF16 && !out->quad;
-  const bool paged16 = out->mat || out->quad;      // tiles of 8 KiB K + 8 KiB V in whole pages
-  const int tile_tokens = paged16 ? (8 / (row / 64)) * 16 : 8 * (kWave / (row / 16));
+  // tokens per tile: the matrix-core engine works in tiles of 4 KiB K + 4 KiB V (one 16-token block
+  // for 512-byte rows), the quad engine in 8 + 8 KiB of whole pages, the row engine in 8 loads
+  const int tile_tokens = out->mat    ? std::max(1, 4 / (row / 64)) * 16
+                          : out->quad ? (8 / (row / 64)) * 16
+                                      : 8 * (kWave / (row / 16));
   int64_t max_pages = (int64_t(max_seq_len) + T - 1) / T;
   if (window > 0) max_pages = std::min<int64_t>(max_pages, window / T + 2);
   const int64_t max_tiles = (max_pages * T + tile_tokens - 1) / tile_tokens;
