@@ -44,12 +44,12 @@ struct MatEngine {
   static constexpr int T = 16;                 // tokens per block; a page holds 1/2, 1, 2, 4 or 8 blocks
   static constexpr int ROW = D * 2;            // bytes per token row
   static constexpr int KCH = ROW / 64;         // k-steps of the score product == 1 KiB loads per page
-  // A tile is 4 KiB of K and 4 KiB of V (one 16-token block of 256-byte rows, two of 128-byte
-  // rows) or, for 512-byte rows, the one block of 8 + 8 KiB that cannot be cut.  Tiles of 8 + 8
-  // KiB for the shorter rows measured 1.2-3 % slower over whole steps, tiles of 16 + 16 KiB for
-  // 512-byte rows 2.3 %: the fewer bytes a wavefront keeps in flight, the better, down to the
-  // 16-token block the matrix-core products work on.
-  static constexpr int PPT = KCH >= 4 ? 1 : 4 / KCH;   // blocks per tile
+  // A tile is one 16-token block for rows of 256 and 512 bytes (4 + 4 and 8 + 8 KiB of K and V) and
+  // four blocks for 128-byte rows (8 + 8 KiB).  Measured: two blocks per tile are 1.2-3 % slower
+  // over whole steps for 256-byte rows and 2.3 % for 512-byte rows -- the fewer bytes a wavefront
+  // keeps in flight, the better -- while for 128-byte rows, where a block is only 2 + 2 KiB and the
+  // per-tile softmax weighs more, one or two blocks per tile are 14 % and 3 % slower than four.
+  static constexpr int PPT = KCH >= 4 ? 1 : 4;         // blocks per tile
   static constexpr int NLD = PPT * KCH;        // 16-byte loads per lane and tile, K and V alike
   static constexpr int LPT = ROW / 16;         // V loads: lanes per token row
   static constexpr int TPL = kWave / LPT;      // V loads: token rows per load

@@ -442,9 +442,9 @@ int decode_geometry(const jenga_pool* pool, int32_t kind, int32_t n_q_heads, int
   // to 4 heads per KV head, other fp32 K/V to the general engine.
   out->quad = k.t_log2 == 4 && (G == 1 || G == 2 || G == 4) && row <= 512 && k.desc.dtype == JENGA_F32;
   out->mat = k.desc.dtype == JENGA_BF16 && !out->quad;
-  // tokens per tile: the matrix-core engine works in tiles of 4 KiB K + 4 KiB V (one 16-token block
-  // for 512-byte rows), the quad engine in 8 + 8 KiB of whole pages, the row engine in 8 loads
-  const int tile_tokens = out->mat    ? std::max(1, 4 / (row / 64)) * 16
+  // tokens per tile: the matrix-core engine works in single 16-token blocks (four of them for
+  // 128-byte rows), the quad engine in 8 + 8 KiB of whole pages, the row engine in 8 loads
+  const int tile_tokens = out->mat    ? (row >= 256 ? 1 : 4) * 16
                           : out->quad ? (8 / (row / 64)) * 16
                                       : 8 * (kWave / (row / 16));
   int64_t max_pages = (int64_t(max_seq_len) + T - 1) / T;
