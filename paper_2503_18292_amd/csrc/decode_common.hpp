@@ -95,14 +95,22 @@ __device__ __forceinline__ int chunk_of(int chunk_tiles, int min_chunk_tiles, in
 }
 
 // First request whose inclusive prefix exceeds flat position x (x < W).
+static_assert(kMaxBatch <= kWave * kWave, "find_request searches the runs of 64 requests with one lane each");
 __device__ __forceinline__ int find_request(const int* s_incl, int batch, int x, int lane) {
-  for (int c0 = 0; c0 < batch; c0 += kWave) {
-    const int i = c0 + lane;
-    const bool past = i < batch && s_incl[i] > x;
+  // two rounds whatever the batch: which run of 64 requests, then which request in it
+  // (s_incl is non-decreasing, so the first run whose last entry exceeds x holds the answer)
+  int c0 = 0;
+  if (batch > kWave) {
+    const int n_runs = (batch + kWave - 1) / kWave;        // at most kMaxBatch / kWave = 16
+    const int last = min((lane + 1) * kWave, batch) - 1;
+    const bool past = lane < n_runs && s_incl[last] > x;
     const unsigned long long hit = __ballot(past);
-    if (hit) return c0 + __builtin_ctzll(hit);
+    c0 = (hit ? __builtin_ctzll(hit) : n_runs - 1) * kWave;
   }
-  return batch - 1;
+  const int i = c0 + lane;
+  const bool past = i < batch && s_incl[i] > x;
+  const unsigned long long hit = __ballot(past);
+  return hit ? c0 + __builtin_ctzll(hit) : batch - 1;
 }
 
 // ---- cross-lane helpers ------------------------------------------------------------

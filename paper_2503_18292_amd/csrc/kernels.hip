@@ -66,8 +66,10 @@ __global__ __launch_bounds__(kWave) void decode_partial_kernel(const DecodeParam
   if (x0 >= W) return;
   int x = int(x0);
   const int x1 = int(min<int64_t>(W, x0 + C));
+  int b = find_request(s_incl, p.batch, x, lane);
   while (x < x1) {
-    const int b = find_request(s_incl, p.batch, x, lane);
+    // x only grows: the request of the next segment is the same one or a later one
+    while (b < p.batch - 1 && s_incl[b] <= x) ++b;
     const int start_b = b > 0 ? s_incl[b - 1] : 0;
     const int units_b = (s_incl[b] - start_b) / p.n_kv_heads;     // start-up units + tiles, per head
     const int rem = x - start_b;
