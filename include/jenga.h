@@ -291,8 +291,7 @@ int64_t jenga_decode_workspace_bytes(const jenga_pool* pool, int32_t kind, int32
  *   workspace    device, >= jenga_decode_workspace_bytes(...), 16-byte aligned, caller-owned;
  *                holds per-partition (max, sum, accumulator) between the two kernels
  * Runs the partial kernel and the split-K reduction on `stream`.
- * Errors: INVALID, ALIGN, WORKSPACE, UNSUPPORTED (G > 16 with bf16 K/V, G not in {1,2,4,8} with
- * fp32 K/V; batch > 1024), HIP. */
+ * Errors: INVALID, ALIGN, WORKSPACE, UNSUPPORTED (G > 16; batch > 1024), HIP. */
 int jenga_paged_decode(const jenga_pool* pool, int32_t kind, int32_t layer,
                        const void* q, int32_t n_q_heads,
                        const void* k_new, const void* v_new,

@@ -1,5 +1,5 @@
-// Shared by the decode engines (device code, gfx950): launch parameters, the flat work
-// partitioning, cross-lane helpers, element types, page-id registers and the partial record.
+// Shared by the decode kernel's front end and engine (device code, gfx950): launch parameters,
+// the flat work partitioning, element types and the page-id registers.
 // Included by kernels.hip only; everything lives in that file's unnamed namespace.
 #pragma once
 
@@ -113,53 +113,6 @@ __device__ __forceinline__ int find_request(const int* s_incl, int batch, int x,
   return hit ? c0 + __builtin_ctzll(hit) : batch - 1;
 }
 
-// ---- cross-lane helpers ------------------------------------------------------------
-template <int CTRL>
-__device__ __forceinline__ float dpp_add(float x) {
-  const int y = __builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true);
-  return x + __int_as_float(y);
-}
-
-template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ float dpp_max(float x) {
-  const int y = __builtin_amdgcn_update_dpp(__float_as_int(x), __float_as_int(x), CTRL, ROW_MASK, 0xf, false);
-  return fmaxf(x, __int_as_float(y));
-}
-
-// Maximum over the wave, in an SGPR-uniform value.
-__device__ __forceinline__ float wave_max(float x) {
-  x = dpp_max<0xB1, 0xf>(x);    // lane ^ 1
-  x = dpp_max<0x4E, 0xf>(x);    // lane ^ 2
-  x = dpp_max<0x124, 0xf>(x);   // row_ror:4
-  x = dpp_max<0x128, 0xf>(x);   // row_ror:8  -> every lane holds its row's maximum
-  x = dpp_max<0x142, 0xa>(x);   // row_bcast:15 into rows 1 and 3
-  x = dpp_max<0x143, 0xc>(x);   // row_bcast:31 into rows 2 and 3 -> lane 63 holds the maximum
-  return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(x), kWave - 1));
-}
-
-// Sum over aligned groups of LANES lanes, result in every lane of the group.
-template <int LANES>
-__device__ __forceinline__ float group_sum(float x) {
-  static_assert(LANES == 8 || LANES == 16 || LANES == 32 || LANES == 64, "group size");
-  x = dpp_add<0xB1>(x);    // quad_perm [1,0,3,2]: lane ^ 1
-  x = dpp_add<0x4E>(x);    // quad_perm [2,3,0,1]: lane ^ 2
-  x = dpp_add<0x141>(x);   // row_half_mirror: the other quad of each 8 lanes
-  if constexpr (LANES >= 16) x = dpp_add<0x140>(x);   // row_mirror: the other half of each 16 lanes
-  if constexpr (LANES >= 32) {
-    // v_permlane16_swap exchanges odd rows of the first operand with even rows of the second;
-    // fed the same value twice, the two results hold each row and its neighbour row.
-    const unsigned u = __float_as_uint(x);
-    const auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
-    x = __uint_as_float(r[0]) + __uint_as_float(r[1]);
-  }
-  if constexpr (LANES >= 64) {
-    const unsigned u = __float_as_uint(x);
-    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-    x = __uint_as_float(r[0]) + __uint_as_float(r[1]);
-  }
-  return x;
-}
-
 // ---- element types ---------------------------------------------------------------
 struct F32 {
   static constexpr int kBytes = 4;
@@ -168,52 +121,13 @@ struct BF16 {
   static constexpr int kBytes = 2;
 };
 
-typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));   // 16 bytes; a native vector, so it can be loaded non-temporally
-
-// <k, q> over the 16 bytes a lane holds.
-template <typename E>
-__device__ __forceinline__ float dot16(const u32x4& k, const u32x4& q) {
-  if constexpr (E::kBytes == 4) {
-    float s = __uint_as_float(k.x) * __uint_as_float(q.x);
-    s = fmaf(__uint_as_float(k.y), __uint_as_float(q.y), s);
-    s = fmaf(__uint_as_float(k.z), __uint_as_float(q.z), s);
-    s = fmaf(__uint_as_float(k.w), __uint_as_float(q.w), s);
-    return s;
-  } else {
-    // v_dot2_f32_bf16: two bf16 products accumulated in fp32 per instruction.  The words are
-    // copied to scalars first: a bit cast applied directly to a vector element read the
-    // first element every time with this compiler.
-    const unsigned kw[4] = {k.x, k.y, k.z, k.w};
-    const unsigned qw[4] = {q.x, q.y, q.z, q.w};
-    float s = 0.f;
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, kw[i]),
-                                          __builtin_bit_cast(bf16x2_t, qw[i]), s, false);
-    return s;
-  }
-}
-
-// The 16 bytes of a lane as fp32 values (4 for fp32 storage, 8 for bf16).
-template <typename E>
-__device__ __forceinline__ void unpack16(const u32x4& v, float* f) {
-  if constexpr (E::kBytes == 4) {
-    f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y);
-    f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
-  } else {
-    f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xffff0000u);
-    f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xffff0000u);
-    f[4] = __uint_as_float(v.z << 16); f[5] = __uint_as_float(v.z & 0xffff0000u);
-    f[6] = __uint_as_float(v.w << 16); f[7] = __uint_as_float(v.w & 0xffff0000u);
-  }
-}
 
 // Page ids of the pages a wavefront is about to read, 128 at a time in two registers: lane j
 // of register (c & 1) holds the id of page 64*c + j (relative to the first page).  A
-// v_readlane turns one into a scalar, which makes the page's base address scalar too.  The
-// K stream runs one tile ahead of the V stream, so when K enters chunk c the register of
-// chunk c+1 (== that of chunk c-1, which V has just left) is reloaded.
+// v_readlane turns one into a scalar, which makes the page's base address scalar too.  When
+// the K and V requests of a tile enter run c of 64 pages, the register of run c+1 (== that of
+// run c-1, which they have just left) is reloaded.
 struct PageIds {
   const int32_t* row;   // block-table entry of relative page 0
   int n_pages;
@@ -232,11 +146,6 @@ struct PageIds {
     reg0 = fetch(0);
     reg1 = fetch(kWave);
   }
-  // true when the table entry itself is a page of the pool (used before writing into it)
-  __device__ __forceinline__ bool writable(int page_rel) const {
-    const int raw = row[page_rel];
-    return raw >= 0 && raw <= max_id;
-  }
   __device__ __forceinline__ int get(int page_rel) const {
     const int r = (page_rel & kWave) ? reg1 : reg0;
     return __builtin_amdgcn_readlane(r, page_rel & (kWave - 1));
@@ -250,24 +159,5 @@ struct PageIds {
     }
   }
 };
-
-// Writes one partial record.  acc lives in the V lane geometry: lanes [0, LPT) hold EPL
-// consecutive output elements each.
-template <int D, int G, int EPL>
-__device__ __forceinline__ void store_partial(const DecodeParams& p, int64_t slot, int lane, int lpt,
-                                              const float (&m)[G], const float (&l)[G],
-                                              const float (&acc)[G][EPL]) {
-  if (lane < lpt) {
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-      float* dst = p.ws_acc + (slot * G + g) * D + lane * EPL;
-#pragma unroll
-      for (int j = 0; j < EPL; j += 4)
-        *reinterpret_cast<float4*>(dst + j) =
-            make_float4(acc[g][j], acc[g][j + 1], acc[g][j + 2], acc[g][j + 3]);
-      if (lane == 0) *reinterpret_cast<float2*>(p.ws_ml + (slot * G + g) * 2) = make_float2(m[g], l[g]);
-    }
-  }
-}
 
 }  // namespace

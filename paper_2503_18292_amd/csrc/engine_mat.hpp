@@ -1,16 +1,16 @@
-// Decode engine on the matrix cores: bf16 K/V, any page size (see kernels.hip for the front end).
+// Decode engine on the matrix cores: bf16 and fp32 K/V, any page size (see kernels.hip for the front end).
 #pragma once
 
 #include "decode_common.hpp"
 
 namespace {
 
-// ---- engine for bf16 K/V: both contractions on the matrix cores ----------------------------
+// ---- both contractions of a 16-token block on the matrix cores ------------------------------
 //
 // The work per 16-token block is a small dense contraction, scores = K[16 x D] . Q^T[D x G] and
 // out += P[G x 16] . V[16 x D], and the matrix cores take it off the vector ALUs altogether:
-// with 8 heads on every K/V byte those can no longer keep up with HBM (the quad engine would
-// need about 70 vector instructions per KiB), and with fewer heads the loads still issue
+// with 8 heads on every K/V byte those can no longer keep up with HBM (an engine on the vector
+// ALUs needed about 70 instructions per KiB), and with fewer heads the loads still issue
 // earlier and more evenly when so little else competes for the issue slots.  The G heads are
 // padded to the 16 rows / columns of the instructions, so any number from 1 to 16 can be served:
 // G_ = 0 is a build that takes it at run time (3, 5, 6, 7 ... heads per KV head), the powers of
@@ -21,7 +21,7 @@ namespace {
 // rows 4j .. 4j+3.
 //   scores  v_mfma_f32_16x16x32_bf16, A = K page (row = token, k = d): lane (n, j) reads the
 //           16 bytes at d = 8j of each 64-byte piece of token n's row -- a plain 16-byte load,
-//           64-byte runs per token as in the quad engine.  B = Q (column = head, zero for the
+//           64-byte runs per token.  B = Q (column = head, zero for the
 //           padding heads).  Result: lane (n, j) holds head n, tokens 4j .. 4j+3 of the page.
 //   values  v_mfma_f32_16x16x16_bf16, A = P (row = head, k = token of the page): exactly the
 //           four probabilities lane (n, j) holds after the softmax.  B = V (k = token,
@@ -36,13 +36,20 @@ namespace {
 // cores are idle most of the time anyway.
 // HALF_: the pages hold 8 tokens, half a block (a build of its own, so that the usual case keeps
 // a scalar page address plus a constant lane offset for every load).
-template <int D_, int G_, bool HALF_>
+// fp32 K/V takes the same road with v_mfma_f32_16x16x4_f32 (A row n / B column n, k = j; result as
+// above): lane (n, j) holds the four floats d = 16c + 4j + e of token n from each 16-byte load, and
+// since the order inside the contraction is free, product (c, e) pairs them with the same four
+// floats of the query rows.  For the values, product s of a block contracts over tokens 4j + s:
+// the probability is register s of the lane's score result, and V[4j + s][16 blk + n] is one float
+// per lane, read from the row-major LDS copy with an ordinary 4-byte read.
+template <typename E_, int D_, int G_, bool HALF_>
 struct MatEngine {
-  using E = BF16;
+  using E = E_;
+  static constexpr bool F32K = E::kBytes == 4;
   static constexpr int D = D_;
   static_assert(G_ >= 0 && G_ <= 16, "heads are padded to 16");
   static constexpr int T = 16;                 // tokens per block; a page holds 1/2, 1, 2, 4 or 8 blocks
-  static constexpr int ROW = D * 2;            // bytes per token row
+  static constexpr int ROW = D * E::kBytes;    // bytes per token row
   static constexpr int KCH = ROW / 64;         // k-steps of the score product == 1 KiB loads per page
   // A tile is one 16-token block for rows of 256 and 512 bytes (4 + 4 and 8 + 8 KiB of K and V) and
   // four blocks for 128-byte rows (8 + 8 KiB).  Measured: two blocks per tile are 1.2-3 % slower
@@ -54,10 +61,10 @@ struct MatEngine {
   static constexpr int LPT = ROW / 16;         // V loads: lanes per token row
   static constexpr int TPL = kWave / LPT;      // V loads: token rows per load
   static constexpr int NBLK = D / 16;          // 16-wide blocks of the output row
-  static constexpr int LROW = ROW + 32;        // LDS row pitch: 8 banks further per row
+  static constexpr int LROW = ROW + (F32K ? 16 : 32);   // LDS row pitch: rows 4 apart land 16 banks apart (fp32: 4-byte reads), rows 1 apart 8 banks (bf16: transposing reads)
   static constexpr int kTileLog2 = PPT == 1 ? 4 : PPT == 2 ? 5 : 6;
   static constexpr int kLdsFloats = PPT * T * LROW / 4;
-  static_assert(KCH == 2 || KCH == 4 || KCH == 8, "row size");
+  static_assert(KCH == 2 || KCH == 4 || KCH == 8 || KCH == 16, "row size");
 
   typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
   typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
@@ -115,14 +122,13 @@ struct MatEngine {
     const unsigned lds_rd = (4 * j + (n >> 2)) * LROW + (n & 3) * 8;     // transposed read (+ page, + block)
 
     // B operand of the score product: head n (zero rows for the padding heads)
-    bf16x8 qb[KCH];
+    u32x4 qb[KCH];
 #pragma unroll
     for (int c = 0; c < KCH; ++c) {
-      u32x4 w = u32x4{0, 0, 0, 0};
+      qb[c] = u32x4{0, 0, 0, 0};
       if (n < G)
-        w = *reinterpret_cast<const u32x4*>(static_cast<const char*>(p.q) +
-                                           (int64_t(b) * p.n_q_heads + kvh * G + n) * ROW + j * 16 + c * 64);
-      qb[c] = __builtin_bit_cast(bf16x8, w);
+        qb[c] = *reinterpret_cast<const u32x4*>(static_cast<const char*>(p.q) +
+                                               (int64_t(b) * p.n_q_heads + kvh * G + n) * ROW + j * 16 + c * 64);
     }
 
     float m = kNegBig, l = 0.f;        // of head n; l is this lane's share (its tokens only)
@@ -262,9 +268,17 @@ struct MatEngine {
       for (int pp = 0; pp < PPT; ++pp) {
         s[pp] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-        for (int c = 0; c < KCH; ++c)
-          s[pp] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kbuf[pp * KCH + c]), qb[c],
-                                                          s[pp], 0, 0, 0);
+        for (int c = 0; c < KCH; ++c) {
+          if constexpr (F32K) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              s[pp] = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(kbuf[pp * KCH + c][e]),
+                                                           __uint_as_float(qb[c][e]), s[pp], 0, 0, 0);
+          } else {
+            s[pp] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kbuf[pp * KCH + c]),
+                                                            __builtin_bit_cast(bf16x8, qb[c]), s[pp], 0, 0, 0);
+          }
+        }
       }
 
       if (tile + 1 < n_tiles) {
@@ -296,6 +310,7 @@ struct MatEngine {
       const float m_new = fmaxf(m, across_groups_max(mx));
       const float alpha = __builtin_amdgcn_exp2f(m - m_new);
       bf16x4 prob_hi[PPT], prob_lo[PPT];
+      float prob[PPT][4];
       float sum = 0.f;
 #pragma unroll
       for (int pp = 0; pp < PPT; ++pp)
@@ -303,9 +318,13 @@ struct MatEngine {
         for (int i = 0; i < 4; ++i) {
           float e = __builtin_amdgcn_exp2f(s[pp][i] - m_new);
           if (!clean) e = (s[pp][i] == kNegBig) ? 0.f : e;
-          const __bf16 hi = static_cast<__bf16>(e);
-          prob_hi[pp][i] = hi;
-          prob_lo[pp][i] = static_cast<__bf16>(e - static_cast<float>(hi));
+          if constexpr (F32K) {
+            prob[pp][i] = e;
+          } else {
+            const __bf16 hi = static_cast<__bf16>(e);
+            prob_hi[pp][i] = hi;
+            prob_lo[pp][i] = static_cast<__bf16>(e - static_cast<float>(hi));
+          }
           sum += e;
         }
       l = fmaf(l, alpha, sum);
@@ -331,11 +350,19 @@ struct MatEngine {
       for (int pp = 0; pp < PPT; ++pp)
 #pragma unroll
         for (int blk = 0; blk < NBLK; ++blk) {
-          const s16x4 v4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-              (lds_s16x4_ptr)(v_lds + pp * T * LROW + lds_rd + blk * 32));
-          const bf16x4 vt = __builtin_bit_cast(bf16x4, v4);
-          acc[blk] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(prob_hi[pp], vt, acc[blk], 0, 0, 0);
-          acc[blk] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(prob_lo[pp], vt, acc[blk], 0, 0, 0);
+          if constexpr (F32K) {
+#pragma unroll
+            for (int s4 = 0; s4 < 4; ++s4) {
+              const float vt = *reinterpret_cast<const float*>(v_lds + (pp * T + 4 * j + s4) * LROW + (16 * blk + n) * 4);
+              acc[blk] = __builtin_amdgcn_mfma_f32_16x16x4f32(prob[pp][s4], vt, acc[blk], 0, 0, 0);
+            }
+          } else {
+            const s16x4 v4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (lds_s16x4_ptr)(v_lds + pp * T * LROW + lds_rd + blk * 32));
+            const bf16x4 vt = __builtin_bit_cast(bf16x4, v4);
+            acc[blk] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(prob_hi[pp], vt, acc[blk], 0, 0, 0);
+            acc[blk] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(prob_lo[pp], vt, acc[blk], 0, 0, 0);
+          }
         }
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
       __builtin_amdgcn_wave_barrier();

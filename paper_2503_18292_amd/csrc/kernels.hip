@@ -10,12 +10,10 @@
 // Decode attention is bandwidth-bound (G flop per byte of bf16 K/V).  What decides the speed
 // is (1) that every wavefront always has KiB-sized loads in flight, (2) that no wavefront
 // idles while others still work (work is cut into equal pieces, not into per-request pieces),
-// and (3) that the arithmetic stays out of the way of the loads.  Three engines share the
-// front end: the matrix-core engine (bf16 K/V, any page size: both products of a 16-token
-// block are small dense contractions and go through MFMA, which leaves the vector ALUs almost
-// idle and is what keeps 8 and 16 heads per KV head at the HBM rate), the quad engine
-// (fp32 K/V in 16-token pages, on the vector ALUs), and the general row engine (the rest of
-// fp32).
+// and (3) that the arithmetic stays out of the way of the loads: both products of a 16-token
+// block are small dense contractions and go through MFMA (bf16 and fp32 K/V alike, any page
+// size, 1 to 16 query heads per KV head), which leaves the vector ALUs almost idle and keeps
+// even 16 heads per KV head at the HBM rate.
 //
 // The kernel view of the pool is the one of paper Sec. 4.2: a start pointer (pool base +
 // layer offset), a page stride (the kind's small-page size) and page ids (the kind's block
@@ -47,8 +45,6 @@
 #include "pool_internal.hpp"
 #include "decode_common.hpp"
 #include "engine_mat.hpp"
-#include "engine_quad.hpp"
-#include "engine_row.hpp"
 
 namespace {
 
@@ -327,51 +323,26 @@ bool attention_kind(const jenga::Kind& k) {
 
 bool aligned16(const void* p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; }
 
-// Only the combinations decode_geometry() can ask for are instantiated.
-template <int D, bool HALF>
-DecodeFn pick_mat(int G) {
+// Builds: element type x head size x page kind (8-token pages are half blocks) x head count
+// (the powers of two at compile time, 0 = any other count up to 16 at run time).
+template <typename E, int D, bool HALF>
+DecodeFn pick_g(int G) {
   switch (G) {
-    case 1: return decode_partial_kernel<MatEngine<D, 1, HALF>>;
-    case 2: return decode_partial_kernel<MatEngine<D, 2, HALF>>;
-    case 4: return decode_partial_kernel<MatEngine<D, 4, HALF>>;
-    case 8: return decode_partial_kernel<MatEngine<D, 8, HALF>>;
-    case 16: return decode_partial_kernel<MatEngine<D, 16, HALF>>;
-    default: return decode_partial_kernel<MatEngine<D, 0, HALF>>;     // any other count up to 16, at run time
+    case 1: return decode_partial_kernel<MatEngine<E, D, 1, HALF>>;
+    case 2: return decode_partial_kernel<MatEngine<E, D, 2, HALF>>;
+    case 4: return decode_partial_kernel<MatEngine<E, D, 4, HALF>>;
+    case 8: return decode_partial_kernel<MatEngine<E, D, 8, HALF>>;
+    case 16: return decode_partial_kernel<MatEngine<E, D, 16, HALF>>;
+    default: return decode_partial_kernel<MatEngine<E, D, 0, HALF>>;
   }
-}
-
-template <typename E, int D>
-DecodeFn pick_g(bool mat, bool half_pages, bool quad, int G) {
-  constexpr int kRow = D * E::kBytes;
-  if constexpr (E::kBytes == 2) {
-    if (mat) return half_pages ? pick_mat<D, true>(G) : pick_mat<D, false>(G);
-  }
-  if constexpr (kRow <= 512 && E::kBytes == 4) {
-    if (quad) {
-      switch (G) {
-        case 1: return decode_partial_kernel<QuadEngine<E, D, 1>>;
-        case 2: return decode_partial_kernel<QuadEngine<E, D, 2>>;
-        default: return decode_partial_kernel<QuadEngine<E, D, 4>>;
-      }
-    }
-  }
-  if constexpr (E::kBytes == 4) {
-    switch (G) {
-      case 1: return decode_partial_kernel<RowEngine<E, D, 1>>;
-      case 2: return decode_partial_kernel<RowEngine<E, D, 2>>;
-      case 4: return decode_partial_kernel<RowEngine<E, D, 4>>;
-      default: return decode_partial_kernel<RowEngine<E, D, 8>>;
-    }
-  }
-  return nullptr;      // not reached: every bf16 shape has been dispatched above
 }
 
 template <typename E>
-DecodeFn pick_d(int D, bool mat, bool half_pages, bool quad, int G) {
+DecodeFn pick_d(int D, bool half_pages, int G) {
   switch (D) {
-    case 64: return pick_g<E, 64>(mat, half_pages, quad, G);
-    case 128: return pick_g<E, 128>(mat, half_pages, quad, G);
-    default: return pick_g<E, 256>(mat, half_pages, quad, G);
+    case 64: return half_pages ? pick_g<E, 64, true>(G) : pick_g<E, 64, false>(G);
+    case 128: return half_pages ? pick_g<E, 128, true>(G) : pick_g<E, 128, false>(G);
+    default: return half_pages ? pick_g<E, 256, true>(G) : pick_g<E, 256, false>(G);
   }
 }
 
@@ -407,8 +378,6 @@ int resident_partitions(DecodeFn fn) noexcept {
 struct Geometry {
   const jenga::Kind* kind;
   int G;
-  bool quad;             // 16-token pages, vector-ALU engine
-  bool mat;              // bf16, matrix-core engine
   int chunk_tiles;       // 0: automatic
   int min_chunk_tiles;
   int n_part_bound;      // partitions the workspace must have room for
@@ -430,33 +399,23 @@ int decode_geometry(const jenga_pool* pool, int32_t kind, int32_t n_q_heads, int
   if (batch > kMaxBatch) return JENGA_ERR_UNSUPPORTED;
   if (n_q_heads % k.desc.n_kv_heads != 0) return JENGA_ERR_INVALID;
   const int G = n_q_heads / k.desc.n_kv_heads;
-  // bf16 K/V: any number of query heads per KV head up to 16 (the matrix-core engine pads them to
-  // 16 anyway); fp32 K/V: the head counts the vector-ALU engines are built for
-  const bool pow2_le8 = G == 1 || G == 2 || G == 4 || G == 8;
-  if (k.desc.dtype == JENGA_BF16 ? G > 16 : !pow2_le8) return JENGA_ERR_UNSUPPORTED;
+  // any number of query heads per KV head up to 16: the engine pads them to the 16 rows of the
+  // matrix-core instructions anyway
+  if (G > 16) return JENGA_ERR_UNSUPPORTED;
   const int row = k.desc.head_dim * k.elem_bytes;
   const int T = k.desc.tokens_per_page;
   out->kind = &k;
   out->G = G;
-  // bf16 K/V goes to the matrix-core engine (on 16-token pages of 256-element rows with 2 query
-  // heads per KV head the quad engine is within 0.3 % of it: 0.7 % ahead while K ran two tiles
-  // ahead, 0.25 % behind since it runs one); fp32 K/V in 16-token pages goes to the quad engine up
-  // to 4 heads per KV head, other fp32 K/V to the general engine.
-  out->quad = k.t_log2 == 4 && (G == 1 || G == 2 || G == 4) && row <= 512 && k.desc.dtype == JENGA_F32;
-  out->mat = k.desc.dtype == JENGA_BF16 && !out->quad;
-  // tokens per tile: the matrix-core engine works in single 16-token blocks (four of them for
-  // 128-byte rows), the quad engine in 8 + 8 KiB of whole pages, the row engine in 8 loads
-  const int tile_tokens = out->mat    ? (row >= 256 ? 1 : 4) * 16
-                          : out->quad ? (8 / (row / 64)) * 16
-                                      : 8 * (kWave / (row / 16));
+  // tokens per tile: one 16-token block, four of them for 128-byte rows
+  const int tile_tokens = (row >= 256 ? 1 : 4) * 16;
   int64_t max_pages = (int64_t(max_seq_len) + T - 1) / T;
   if (window > 0) max_pages = std::min<int64_t>(max_pages, window / T + 2);
   const int64_t max_tiles = (max_pages * T + tile_tokens - 1) / tile_tokens;
   const int64_t w_max = (max_tiles + kSegStartUnits) * k.desc.n_kv_heads * std::max(batch, 1);
   if (w_max > 0x3fffffff) return JENGA_ERR_UNSUPPORTED;
   const bool half_pages = k.t_log2 == 3;
-  out->fn = k.desc.dtype == JENGA_F32 ? pick_d<F32>(k.desc.head_dim, out->mat, half_pages, out->quad, G)
-                                      : pick_d<BF16>(k.desc.head_dim, out->mat, half_pages, out->quad, G);
+  out->fn = k.desc.dtype == JENGA_F32 ? pick_d<F32>(k.desc.head_dim, half_pages, G)
+                                      : pick_d<BF16>(k.desc.head_dim, half_pages, G);
   if (out->fn == nullptr) return JENGA_ERR_UNSUPPORTED;
   const int64_t tile_bytes = int64_t(tile_tokens) * row * 2;
   out->min_chunk_tiles = int(std::max<int64_t>(1, (64 * 1024) / tile_bytes));

@@ -16,7 +16,7 @@ MAX_BATCH = 1024      # stated in the header of the decode entry points
 
 @pytest.mark.parametrize("batch,T,dtype,D,G,window", [
     (MAX_BATCH, 16, "bf16", 128, 4, 0),      # matrix-core engine
-    (MAX_BATCH, 32, "f32", 64, 2, 40),       # row engine, sliding window
+    (MAX_BATCH, 32, "f32", 64, 2, 40),       # fp32 K/V, 32-token pages, sliding window
     (65, 16, "bf16", 256, 2, 0),             # 512-byte rows, one page per tile; one request past a full round of the length scan
     (200, 16, "f32", 64, 1, 0),
 ])

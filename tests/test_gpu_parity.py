@@ -127,7 +127,7 @@ def test_all_built_shapes_full_attention(dtype, D, G):
     (64, "bf16", 128, 4, 0), (64, "f32", 128, 2, 70), (128, "bf16", 64, 2, 0), (128, "f32", 256, 1, 300),
     (8, "f32", 256, 2, 9)])
 def test_other_page_sizes(T, dtype, D, G, window):
-    """Pages of 8, 32, 64 and 128 tokens: the matrix-core engine for bf16, the general (row) engine for fp32."""
+    """Pages of 8, 32, 64 and 128 tokens, bf16 and fp32 K/V."""
     print(f"[case] T={T} {dtype} D={D} G={G} W={window}", flush=True)
     cfg = custom_cfg(dtype, D, 2 * G, 2, WINDOW if window else FULL, window=window, hi=900, T=T)
     for pps in (0, 2):
@@ -153,6 +153,24 @@ def test_matrix_core_engine_shapes(D, G, window, pps, T):
     print(f"[case] matrix-core D={D} G={G} W={window} pps={pps} T={T}", flush=True)
     cfg = custom_cfg("bf16", D, 2 * G, 2, WINDOW if window else FULL, window=window, batch=7, lo=0, hi=1300, T=T)
     r = _runner(cfg, 500 + D + G, pages_per_split=pps,
+                ctx=np.array([0, 1, 15, 16, 31, 1299, 640]))
+    prepare(r)
+    r.device_step()
+    check_against_oracle(r, cfg.name)
+    check_append_landed(r)
+    r.close()
+
+
+@pytest.mark.parametrize("D,G,window,pps,T", [
+    (64, 1, 0, 0, 16), (64, 8, 70, 2, 16), (128, 2, 0, 0, 16), (128, 8, 0, 3, 16), (128, 16, 200, 0, 16),
+    (256, 2, 0, 1, 16), (256, 4, 33, 0, 16), (256, 16, 0, 0, 16), (128, 3, 0, 0, 16), (64, 7, 21, 1, 32),
+    (128, 5, 0, 2, 8), (256, 1, 0, 0, 8), (64, 4, 0, 0, 128), (128, 12, 130, 0, 64), (256, 6, 0, 5, 32)])
+def test_matrix_core_engine_shapes_fp32(D, G, window, pps, T):
+    """fp32 K/V through the fp32 matrix-core products: the same ragged lengths, head counts 1 to 16,
+    pages of 8 to 128 tokens, rows of 256 bytes to 1 KiB."""
+    print(f"[case] matrix-core fp32 D={D} G={G} W={window} pps={pps} T={T}", flush=True)
+    cfg = custom_cfg("f32", D, 2 * G, 2, WINDOW if window else FULL, window=window, batch=7, lo=0, hi=1300, T=T)
+    r = _runner(cfg, 900 + D + G, pages_per_split=pps,
                 ctx=np.array([0, 1, 15, 16, 31, 1299, 640]))
     prepare(r)
     r.device_step()
@@ -232,9 +250,13 @@ def test_peaked_softmax_large_scores(dtype, D, G, T):
             K, V = r.contiguous_kv(k, layer, b)
             want = decode_attention_one(q[b], K.double().numpy(), V.double().numpy(), r.scale(k), 0)
             assert np.isfinite(got[b]).all()
-            # outputs are of the magnitude of V here: relative tolerance only
+            # outputs are of the magnitude of V here: relative tolerance only.  fp32: a score of
+            # magnitude 2^9 .. 2^10 in the base-2 domain has a spacing of 2^-14 = 6.1e-5, so a weight
+            # exp2(s - m) carries a relative error of up to half that times ln 2 = 2.1e-5 from the
+            # rounding of the score alone, whatever the order of the summation; 4e-5 leaves a factor
+            # of two for the accumulation.
             rel = np.linalg.norm(got[b] - want) / np.linalg.norm(want)
-            assert rel <= (1e-5 if dtype == "f32" else TOL_BF16_REL), rel
+            assert rel <= (4e-5 if dtype == "f32" else TOL_BF16_REL), rel
     r.close()
 
 

@@ -16,7 +16,7 @@ def draw_case(seed):
     dtype = rng.choice(["bf16", "bf16", "f32"])
     D = int(rng.choice([64, 128, 256]))
     T = int(rng.choice([16, 16, 16, 8, 32, 64, 128]))
-    G = int(rng.choice([1, 2, 4, 8] + ([16, 3, 5, 6, 7, 12] if dtype == "bf16" else [])))
+    G = int(rng.choice([1, 2, 4, 8, 16, 3, 5, 6, 7, 12]))
     Hkv = int(rng.choice([1, 2, 3]))
     window = int(rng.choice([0, 0, rng.integers(1, 400)]))
     # partitions of 150 and 1000 pages make one wavefront walk through several runs of 64 pages

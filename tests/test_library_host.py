@@ -230,13 +230,13 @@ def test_partition_geometry_and_workspace_queries():
     with pytest.raises(J.JengaError) as e:
         lib.decode_workspace_bytes(0, 20, 64, 8193)       # not a multiple of the 8 KV heads
     assert e.value.status == -1
-    # fp32 K/V: 1, 2, 4 or 8
+    # fp32 K/V alike
     tiny_lib = make_library(configs.tiny(), 4)
-    for hq in (6, 32):                                    # 2 KV heads: G = 3, 16
-        with pytest.raises(J.JengaError) as e:
-            tiny_lib.decode_workspace_bytes(0, hq, 4, 256)
-        assert e.value.status == -6
-    assert tiny_lib.decode_workspace_bytes(0, 16, 4, 256) > 0
+    for hq in (6, 16, 32):                                # 2 KV heads: G = 3, 8, 16
+        assert tiny_lib.decode_workspace_bytes(0, hq, 4, 256) > 0
+    with pytest.raises(J.JengaError) as e:
+        tiny_lib.decode_workspace_bytes(0, 34, 4, 256)    # G = 17
+    assert e.value.status == -6
     with pytest.raises(J.JengaError) as e:
         lib.decode_workspace_bytes(0, 16, 5000, 8193)    # batch beyond the kernels' limit
     assert e.value.status == -6
