@@ -280,7 +280,9 @@ int64_t jenga_decode_workspace_bytes(const jenga_pool* pool, int32_t kind, int32
  *                WINDOW kinds only): the append is then done inside the decode kernel -- the
  *                wavefront that reads a request's last page takes the row at position L - 1
  *                from k_new / v_new, stores it into the page, and attends to it -- which saves
- *                the separate jenga_kv_append launch.  Results are identical.
+ *                the separate jenga_kv_append launch (for very large batches of short requests
+ *                the library still runs the append as a launch of its own in front, which is
+ *                faster there).  Results are identical either way.
  *   block_table  device int32 [batch][bt_stride]; every page overlapping Vis_b must be
  *                resident (>= 0); other entries are never read
  *   seq_lens     device int32 [batch], each <= max_seq_len (larger ones are clamped)

@@ -222,29 +222,20 @@ struct MatEngine {
 
     auto step = [&](int tile, u32x4* kbuf, u32x4* vbuf) {
 
-      // fused append: rows of the token at L - 1 come from k_new / v_new and are stored into the page
+      // fused append: the rows of the token at L - 1 come from k_new / v_new (they are stored into
+      // the page after the loop)
       if (tile == append_tile) {
         const int pp_new = r_new - tile * PPT;
-        char* dst = const_cast<char*>(half_base(r_new, row_new >> 3)) + (row_new & 7) * ROW;
-        const bool store = raw_new >= 0 && raw_new <= p.max_page_id;
         if (n == row_new) {
 #pragma unroll
-          for (int c = 0; c < KCH; ++c) {
-            if (store) *reinterpret_cast<u32x4*>(dst + j * 16 + c * 64) = k_app[c];
+          for (int c = 0; c < KCH; ++c)
 #pragma unroll
             for (int pp = 0; pp < PPT; ++pp)
               if (pp == pp_new) kbuf[pp * KCH + c] = k_app[c];
-          }
         }
-        bool mine = false;
 #pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-          if ((i / KCH) * T + (i % KCH) * TPL + v_row == pp_new * T + row_new) {
-            vbuf[i] = v_app;
-            mine = true;
-          }
-        }
-        if (mine && store) *reinterpret_cast<u32x4*>(dst + p.v_offset + (lane % LPT) * 16) = v_app;
+        for (int i = 0; i < NLD; ++i)
+          if ((i / KCH) * T + (i % KCH) * TPL + v_row == pp_new * T + row_new) vbuf[i] = v_app;
       }
 
       const int tile_tok = tok0 + tile * PPT * T;
@@ -369,6 +360,20 @@ struct MatEngine {
     };
 
     for (int tile = 0; tile < n_tiles; ++tile) step(tile, kb, vb);
+
+    // The new token's rows go into their page only now.  Loads and stores share one in-order
+    // counter and the waits are fixed at compile time for the path without stores, so a store
+    // issued inside the step is waited for by the step's own loads: 1.7 us per segment, measured.
+    // (The tile of the new token is the last of its segment, so the page-id registers still hold
+    // its page.)
+    if (append_tile >= 0 && raw_new >= 0 && raw_new <= p.max_page_id) {
+      char* dst = const_cast<char*>(half_base(r_new, row_new >> 3)) + (row_new & 7) * ROW;
+      if (n == row_new) {
+#pragma unroll
+        for (int c = 0; c < KCH; ++c) *reinterpret_cast<u32x4*>(dst + j * 16 + c * 64) = k_app[c];
+      }
+      if (v_row == (row_new & (TPL - 1))) *reinterpret_cast<u32x4*>(dst + p.v_offset + (lane % LPT) * 16) = v_app;
+    }
 
     l = across_groups_sum(l);
     // one partial record: lane (n, j) holds element 16 * blk + n of heads 4j .. 4j+3

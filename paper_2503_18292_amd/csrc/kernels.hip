@@ -578,6 +578,16 @@ int jenga_paged_decode_partial(const jenga_pool* pool, int32_t kind, int32_t lay
   p.ws_ml = ml;
   p.ws_meta = meta;
   const int n_part = launch_partitions(g);
+  // Every appended row costs its wavefront the latency of a store (loads and stores share one
+  // in-order counter): with many short requests -- six or more (request, KV head) segments per
+  // wavefront -- the append is cheaper as a launch of its own in front (batch 1024 with 100-600
+  // tokens: +2.3 % per step; equal at 4 segments per wavefront, 1.2 % slower at 1).
+  if (k_new != nullptr && segments_of(g) >= 6 * int64_t(n_part)) {
+    rc = jenga_kv_append(pool, kind, layer, k_new, v_new, block_table, bt_stride, seq_lens, batch, stream);
+    if (rc != JENGA_OK) return rc;
+    p.k_new = nullptr;
+    p.v_new = nullptr;
+  }
   hipLaunchKernelGGL(g.fn, dim3(unsigned(n_part)), dim3(kWave), 0, static_cast<hipStream_t>(stream), p);
   return hip_status();
 }

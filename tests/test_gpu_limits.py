@@ -32,6 +32,22 @@ def test_large_batches(batch, T, dtype, D, G, window):
     r.close()
 
 
+@pytest.mark.parametrize("dtype,window", [("bf16", 0), ("f32", 50)])
+def test_many_segments_per_wavefront_append_runs_in_front(dtype, window):
+    """Batch 1024 with 8 KV heads: 8192 (request, KV head) segments for 1024 wavefronts, where the
+    library runs the append as a launch of its own in front of the decode kernel although the new
+    rows were passed to the decode call.  Outputs and pool contents must be what the fused path gives."""
+    print(f"[case] many segments {dtype} W={window}", flush=True)
+    cfg = custom_cfg(dtype, 64, 16, 8, WINDOW if window else FULL, window=window, batch=MAX_BATCH, lo=0, hi=70,
+                     n_layers=1)
+    r = _runner(cfg, 4242)
+    prepare(r)
+    r.device_step()
+    check_against_oracle(r, cfg.name)
+    check_append_landed(r)
+    r.close()
+
+
 def test_batch_above_the_limit_is_refused():
     import paper_2503_18292_amd as J
     cfg = custom_cfg("bf16", 128, 4, 2, FULL, batch=2, n_layers=1)

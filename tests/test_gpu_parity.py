@@ -107,7 +107,7 @@ def custom_cfg(dtype, D, Hq, Hkv, typ, window=0, batch=3, lo=1, hi=700, n_layers
 
 
 SHAPES = [(dt, D, G) for dt in ("bf16", "f32") for D in (64, 128, 256) for G in (1, 2, 4, 8)]
-SHAPES += [("bf16", D, 16) for D in (64, 128, 256)]      # 16 heads per KV head: matrix-core engine only
+SHAPES += [(dt, D, 16) for dt in ("bf16", "f32") for D in (64, 128, 256)]
 
 
 @pytest.mark.parametrize("dtype,D,G", SHAPES)
