@@ -15,14 +15,13 @@ namespace {
 // padded to the 16 rows / columns of the instructions, so any number from 1 to 16 can be served:
 // G_ = 0 is a build that takes it at run time (3, 5, 6, 7 ... heads per KV head), the powers of
 // two have builds of their own (1 % faster: the record stores and query loads are resolved at
-// compile time).  Operand layouts (lane l, n = l % 16,
-// j = l / 16), checked on the device: A holds row n and B holds column n, each with
-// consecutive k (8j .. 8j+7 for 16x16x32, 4j .. 4j+3 for 16x16x16); the result holds column n,
-// rows 4j .. 4j+3.
+// compile time).  Operand layouts (lane l, n = l % 16, j = l / 16), checked on the device: A
+// holds row n and B holds column n, each with consecutive k (8j .. 8j+7 for 16x16x32, 4j .. 4j+3
+// for 16x16x16); the result holds column n, rows 4j .. 4j+3.
 //   scores  v_mfma_f32_16x16x32_bf16, A = K page (row = token, k = d): lane (n, j) reads the
 //           16 bytes at d = 8j of each 64-byte piece of token n's row -- a plain 16-byte load,
-//           64-byte runs per token.  B = Q (column = head, zero for the
-//           padding heads).  Result: lane (n, j) holds head n, tokens 4j .. 4j+3 of the page.
+//           64-byte runs per token.  B = Q (column = head, zero for the padding heads).
+//           Result: lane (n, j) holds head n, tokens 4j .. 4j+3 of the page.
 //   values  v_mfma_f32_16x16x16_bf16, A = P (row = head, k = token of the page): exactly the
 //           four probabilities lane (n, j) holds after the softmax.  B = V (k = token,
 //           column = d) wants four tokens of one column per lane, but V arrives row-major:
@@ -51,8 +50,9 @@ struct MatEngine {
   static constexpr int T = 16;                 // tokens per block; a page holds 1/2, 1, 2, 4 or 8 blocks
   static constexpr int ROW = D * E::kBytes;    // bytes per token row
   static constexpr int KCH = ROW / 64;         // k-steps of the score product == 1 KiB loads per page
-  // A tile is one 16-token block for rows of 256 and 512 bytes (4 + 4 and 8 + 8 KiB of K and V) and
-  // four blocks for 128-byte rows (8 + 8 KiB).  Measured: two blocks per tile are 1.2-3 % slower
+  // A tile is one 16-token block for rows of 256 bytes and more (4 + 4 KiB of K and V, 8 + 8 for
+  // 512-byte rows, 16 + 16 for the 1 KiB rows of 256-element fp32 heads) and four blocks for
+  // 128-byte rows (8 + 8 KiB).  Measured: two blocks per tile are 1.2-3 % slower
   // over whole steps for 256-byte rows and 2.3 % for 512-byte rows -- the fewer bytes a wavefront
   // keeps in flight, the better -- while for 128-byte rows, where a block is only 2 + 2 KiB and the
   // per-tile softmax weighs more, one or two blocks per tile are 14 % and 3 % slower than four.
@@ -61,7 +61,9 @@ struct MatEngine {
   static constexpr int LPT = ROW / 16;         // V loads: lanes per token row
   static constexpr int TPL = kWave / LPT;      // V loads: token rows per load
   static constexpr int NBLK = D / 16;          // 16-wide blocks of the output row
-  static constexpr int LROW = ROW + (F32K ? 16 : 32);   // LDS row pitch: rows 4 apart land 16 banks apart (fp32: 4-byte reads), rows 1 apart 8 banks (bf16: transposing reads)
+  // LDS row pitch: bf16, transposing 8-byte reads of 4 consecutive rows -> 8 banks further per
+  // row; fp32, 4-byte reads of rows 4 apart -> 16 banks further per 4 rows
+  static constexpr int LROW = ROW + (F32K ? 16 : 32);
   static constexpr int kTileLog2 = PPT == 1 ? 4 : PPT == 2 ? 5 : 6;
   static constexpr int kLdsFloats = PPT * T * LROW / 4;
   static_assert(KCH == 2 || KCH == 4 || KCH == 8 || KCH == 16, "row size");
