@@ -298,13 +298,13 @@ class OracleCachingPool(OraclePool):
     equal times the one with the largest prefix length (Sec. 5.1: "the token with the highest
     length is evicted before other tokens").
 
+    A large page is evictable when all its small pages are evictable (Sec. 5.4): one used or
+    one empty small page keeps it out of step 3.  Its LRU time is the latest last access among
+    all its small pages (Sec. 5.4, step 3).
+
     Readings where the paper is silent:
-      * a large page counts as evictable when none of its small pages is used and at least
-        one is evictable (the paper says "all its small pages are evictable"; a large page
-        holding a mix of empty and evictable pages would otherwise be out of reach of step 3
-        although evicting it costs less);
-      * its LRU time is the latest last access among its evictable small pages (Sec. 5.4),
-        ties go to the larger maximum prefix length, then to the lower page number;
+      * ties between large pages of equal LRU time go to the larger maximum prefix length
+        (Sec. 5.1 states the rule for tokens), then to the lower page number;
       * remaining ties between small pages go to the lower id.
     """
 
@@ -397,18 +397,17 @@ class OracleCachingPool(OraclePool):
                 continue
             rk = self.r[ko]
             ids = np.arange(large * rk, (large + 1) * rk)
-            if (self.refcount[ko][ids] > 0).any() or not self.cached[ko][ids].any():
+            if not self.cached[ko][ids].all():       # evictable = every small page evictable
                 continue
-            c = ids[self.cached[ko][ids]]
-            key = (int(self.last_access[ko][c].max()), -int(self.prefix_length[ko][c].max()), large)
+            key = (int(self.last_access[ko][ids].max()), -int(self.prefix_length[ko][ids].max()), large)
             if best_key is None or key < best_key:
                 best, best_key = large, key
         if best is not None:
             ko = int(self.large_kind[best])
             rk = self.r[ko]
-            evicted = [(ko, int(s)) for s in range(best * rk, (best + 1) * rk) if self.cached[ko][s]]
+            evicted = [(ko, int(s)) for s in range(best * rk, (best + 1) * rk)]
             for _, s in evicted:
-                self.cached[ko][s] = False
+                self.cached[ko][s] = False           # "all small pages ... are marked empty"
             self.large_kind[best] = k            # all its small pages are empty now: re-typed
             self.large_req[best] = request
             return self._take_lowest_empty(k, best), evicted

@@ -103,28 +103,74 @@ def test_each_of_the_five_steps_in_order():
     assert b == 4
     c = pool.alloc_evict(1, 3)[0]                                  # last empty large page
     assert c == 2 and pool.free_large() == 0
-    # make large page 0 evictable (both its used pages cached, the other two slots empty)
+    # large page 0 becomes {evictable, evictable, empty, empty}: by the definition of Sec. 5.4
+    # ("evictable if all its small pages are evictable") it is NOT an evictable large page
     for t, sid in enumerate(a):
         pool.set_last_access(0, sid, 10 + t)
         pool.release(0, sid, keep_cached=True)
     # step 1 still wins for request 2 (its own large page has empty slots)
     assert pool.alloc_evict(0, 2) == (5, [])
-    # request 7 has no page of its own and no empty large page exists: step 3 evicts large page 0
-    sid, ev = pool.alloc_evict(0, 7)
-    assert sid == 0 and sorted(ev) == [(0, 0), (0, 1)] and pool.large_owner(0) == (0, 7)
-    # kind 1 for request 8: steps 1-3 fail (nothing evictable), step 4 fails (no empty page of kind 1)
+    # request 7 has no page of its own and no empty large page exists; step 3 finds no evictable
+    # large page (page 0 is mixed), so step 4 hands out an empty slot of another request's page
+    # and nothing is evicted
+    assert pool.alloc_evict(0, 7) == (2, [])
+    assert pool.large_owner(0) == (0, 1)                           # the association stays request 1's
+    assert [pool.state(0, s) for s in range(4)] == [EVICTABLE, EVICTABLE, USED, EMPTY]
+    # kind 1 for request 8: steps 1-3 fail (no evictable large page), 4 and 5 find nothing of kind 1
     with pytest.raises(OutOfPages):
         pool.alloc_evict(1, 8)
-    # step 4: request 9 takes an empty slot that belongs to another request
-    assert pool.alloc_evict(0, 9) == (1, [])
-    # fill kind 0 completely, cache one page in a large page that stays in use, then step 5
-    taken = [pool.alloc_evict(0, 9)[0] for _ in range(4)]
-    assert sorted(taken) == [2, 3, 6, 7]
+    # step 4 again fills the page; released with their contents kept, all four small pages of
+    # large page 0 are evictable and so is the large page
+    assert pool.alloc_evict(0, 7) == (3, [])
+    for sid, t in ((2, 3), (3, 4)):
+        pool.set_last_access(0, sid, t)
+        pool.release(0, sid, keep_cached=True)
+    # step 3: kind 1 evicts large page 0 (all of its small pages are reported) and re-types it
+    sid, ev = pool.alloc_evict(1, 8)
+    assert sid == 0 and sorted(ev) == [(0, 0), (0, 1), (0, 2), (0, 3)] and pool.large_owner(0) == (1, 8)
+    assert [pool.state(0, s) for s in range(4)] == [EMPTY] * 4
+    # kind 0 owns large page 1 only: {used, used, empty, empty}; step 4 fills it for request 9
+    assert [pool.alloc_evict(0, 9) for _ in range(2)] == [(6, []), (7, [])]
     pool.set_last_access(0, 6, 5)
     pool.release(0, 6, keep_cached=True)              # large page 1 still has used pages
     assert pool.alloc_evict(0, 10) == (6, [(0, 6)])   # steps 1-4 fail, step 5 evicts the small page
     with pytest.raises(OutOfPages):
         pool.alloc_evict(0, 10)
+
+
+def test_large_page_is_evictable_only_when_all_its_small_pages_are():
+    """Sec. 5.4: a large page is evictable if all its small pages are evictable.  One empty or one
+    used small page keeps it out of step 3, for its own kind and for any other."""
+    for spoiler in ("empty", "used"):
+        pool = OracleCachingPool(2 * 1024, [256, 1024])
+        x = [pool.alloc(0, 1) for _ in range(4)]      # large page 0, kind 0
+        assert pool.alloc(1, 2) == 1                  # large page 1, kind 1
+        for sid in x[:3]:
+            pool.set_last_access(0, sid, 1)
+            pool.release(0, sid, keep_cached=True)
+        if spoiler == "empty":
+            pool.release(0, x[3], keep_cached=False)
+        with pytest.raises(OutOfPages):               # kind 1 cannot get large page 0
+            pool.alloc_evict(1, 3)
+        if spoiler == "empty":
+            assert pool.alloc_evict(0, 3) == (x[3], [])              # step 4 (empty slot), no eviction
+        else:
+            assert pool.alloc_evict(0, 3) == (x[0], [(0, x[0])])     # step 5: one small page, lowest id among equal keys
+        assert pool.large_owner(0) == (0, 1)
+    # with the fourth page evictable too the large page goes as a whole, its LRU time being the
+    # latest last access among ALL its small pages
+    pool = OracleCachingPool(3 * 1024, [256, 1024])
+    x = [pool.alloc(0, 1) for _ in range(4)]
+    y = [pool.alloc(0, 2) for _ in range(4)]
+    assert pool.alloc(1, 3) == 2
+    for sid, t in zip(x, (1, 1, 1, 8)):
+        pool.set_last_access(0, sid, t)
+    for sid, t in zip(y, (7, 7, 7, 7)):
+        pool.set_last_access(0, sid, t)
+    for sid in x + y:
+        pool.release(0, sid, keep_cached=True)
+    sid, ev = pool.alloc_evict(1, 4)
+    assert sid == 1 and sorted(ev) == [(0, s) for s in y]
 
 
 def test_large_page_lru_uses_latest_access_of_its_small_pages():
