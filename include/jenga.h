@@ -186,9 +186,10 @@ int jenga_block_table_fill(const jenga_pool* pool, int32_t kind, const int64_t* 
  *   4. an empty small page of the kind associated with another request;
  *   5. evict the least recently used evictable small page of the kind.
  * With nothing evictable this is the three-step order of Sec. 4.3.  A large page is evictable
- * when none of its small pages is used and at least one is evictable; its LRU time is the
- * latest last access among its evictable pages.  Among equal times the larger prefix length
- * goes first (Sec. 5.1), then the lower number.  This variant also reports what was evicted,
+ * when all its small pages are evictable (Sec. 5.4: one used or one empty small page keeps it
+ * out of step 3); its LRU time is the latest last access among all its small pages.  Among
+ * equal times the larger prefix length goes first (Sec. 5.1), then the lower number.  After
+ * step 3 every small page of the large page is empty.  This variant also reports what was evicted,
  * so the caller can drop it from its prefix index: up to `capacity` (kind, id) pairs are
  * written to the host arrays (either may be NULL), *out_n_evicted gets the full count. */
 int jenga_alloc_small_evict(jenga_pool* pool, int32_t kind, int64_t request, int32_t* out_small_id,

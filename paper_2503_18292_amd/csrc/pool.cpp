@@ -120,7 +120,9 @@ void drop_from_room_sets(jenga_pool* p, Kind& k, int64_t large) {
 }
 
 // Keeps the large page's membership and key in the evictable-large set in step with its
-// counters: member iff no small page is used and at least one is evictable (Sec. 5.4).
+// counters: member iff all its small pages are evictable (Sec. 5.4).  Its LRU time is the latest
+// last access among all its small pages (Sec. 5.4 step 3); equal times go to the larger maximum
+// prefix length (Sec. 5.1), then to the lower page number.
 void refresh_evictable_large(jenga_pool* p, int64_t large) {
   auto& cur = p->evictable_large_key[large];
   if (std::get<2>(cur) >= 0) {
@@ -128,11 +130,11 @@ void refresh_evictable_large(jenga_pool* p, int64_t large) {
     std::get<2>(cur) = -1;
   }
   const int32_t kind = p->large_kind[large];
-  if (kind < 0 || p->large_used[large] != 0 || p->large_cached[large] == 0) return;
+  if (kind < 0) return;
   const Kind& k = p->kinds[kind];
+  if (int64_t(p->large_cached[large]) != k.per_large) return;
   int64_t ts = std::numeric_limits<int64_t>::min(), len = std::numeric_limits<int64_t>::min();
   for (int64_t s = large * k.per_large; s < (large + 1) * k.per_large; ++s) {
-    if (!bit_get(k.cached, s)) continue;
     ts = std::max(ts, k.last_access.empty() ? 0 : k.last_access[s]);
     len = std::max(len, k.prefix_length.empty() ? 0 : k.prefix_length[s]);
   }
@@ -170,11 +172,9 @@ int32_t take_slot(jenga_pool* p, int32_t kind, int64_t large) {
   const int64_t sid = first_empty(k, large);
   bit_set(k.used, sid);
   ++k.used_small;
-  const bool was_evictable = p->large_used[large] == 0 && p->large_cached[large] > 0;
   ++p->large_used[large];
   if (--p->large_empty[large] == 0) drop_from_room_sets(p, k, large);
-  if (was_evictable) refresh_evictable_large(p, large);
-  return int32_t(sid);
+  return int32_t(sid);      // (a page with an empty slot is not an evictable large page: no set to update)
 }
 
 struct Evicted {
@@ -214,8 +214,7 @@ int alloc_small(jenga_pool* p, int32_t kind, int64_t request, int32_t* out, Evic
     const int64_t large = std::get<2>(*p->evictable_large.begin());
     const int32_t old_kind = p->large_kind[large];
     Kind& ko = p->kinds[old_kind];
-    for (int64_t s = large * ko.per_large; s < (large + 1) * ko.per_large; ++s) {
-      if (!bit_get(ko.cached, s)) continue;
+    for (int64_t s = large * ko.per_large; s < (large + 1) * ko.per_large; ++s) {   // all evictable
       ko.evictable.erase(small_key(ko, int32_t(s)));
       bit_clear(ko.cached, s);
       --ko.cached_small;
@@ -223,8 +222,7 @@ int alloc_small(jenga_pool* p, int32_t kind, int64_t request, int32_t* out, Evic
     }
     p->large_cached[large] = 0;
     refresh_evictable_large(p, large);          // leaves the set
-    drop_from_room_sets(p, ko, large);
-    --ko.owned_large;
+    --ko.owned_large;                           // (it had no empty slot, so it is in no room set)
     p->large_kind[large] = -1;
     adopt_large(p, kind, large, request);
     *out = take_slot(p, kind, large);
@@ -240,14 +238,13 @@ int alloc_small(jenga_pool* p, int32_t kind, int64_t request, int32_t* out, Evic
     const int32_t sid = std::get<2>(*k.evictable.begin());
     k.evictable.erase(k.evictable.begin());
     const int64_t large = sid / k.per_large;
-    const bool was_evictable = p->large_used[large] == 0;
     bit_clear(k.cached, sid);
     --k.cached_small;
     --p->large_cached[large];
     bit_set(k.used, sid);
     ++k.used_small;
     ++p->large_used[large];
-    if (was_evictable) refresh_evictable_large(p, large);
+    refresh_evictable_large(p, large);
     if (ev) ev->add(kind, sid);
     *out = sid;
     return JENGA_OK;
@@ -288,13 +285,10 @@ int release_small(jenga_pool* p, int32_t kind, int32_t sid, bool keep_cached) {
       k.with_room_by_request[p->large_request[large]].insert(large);
     }
   }
-  if (p->large_used[large] == 0) {
-    if (p->large_cached[large] == 0) {
-      return_large(p, large);               // every small page empty (Sec. 4.1 free())
-    } else {
-      refresh_evictable_large(p, large);
-    }
-  }
+  if (p->large_used[large] == 0 && p->large_cached[large] == 0)
+    return_large(p, large);                 // every small page empty (Sec. 4.1 free())
+  else if (keep_cached)
+    refresh_evictable_large(p, large);      // it may have been the last page not yet evictable
   return JENGA_OK;
 }
 
@@ -607,9 +601,8 @@ int jenga_acquire_cached(jenga_pool* pool, int32_t kind, int32_t small_id) {
   ++k.used_small;
   const int64_t large = small_id / k.per_large;
   --pool->large_cached[large];
-  const bool was_evictable = pool->large_used[large] == 0;
   ++pool->large_used[large];
-  if (was_evictable) refresh_evictable_large(pool, large);
+  refresh_evictable_large(pool, large);
   return JENGA_OK;
   });
 }

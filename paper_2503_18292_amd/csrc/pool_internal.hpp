@@ -60,8 +60,8 @@ struct jenga_pool {
   std::vector<int32_t> large_used;        // used slots, valid while owned
   std::vector<int32_t> large_cached;      // evictable slots, valid while owned
   std::set<int64_t> free_large;           // ordered: lowest-numbered first
-  // large pages with no used and at least one evictable small page, ordered by
-  // (latest last access of their evictable pages, -largest prefix length, page number)
+  // large pages whose small pages are all evictable (Sec. 5.4), ordered by
+  // (latest last access of their small pages, -largest prefix length, page number)
   std::set<std::tuple<int64_t, int64_t, int64_t>> evictable_large;
   std::vector<std::tuple<int64_t, int64_t, int64_t>> evictable_large_key;   // key while in the set
   std::unordered_map<int64_t, jenga::RequestPages> requests;

@@ -62,6 +62,37 @@ def test_paper_example_eviction_order_matches_oracle():
     assert e.value.status == -2
 
 
+def test_mixed_large_page_is_not_evicted_as_a_whole():
+    """Sec. 5.4: only a large page whose small pages are ALL evictable is taken by step 3.  The same
+    calls on oracle and library: ids, eviction reports and out-of-pages events agree."""
+    def script(pool):
+        out = []
+        def go(k, req):
+            try:
+                out.append(pool.alloc_evict(k, req))
+            except (OutOfPages, J.JengaError):
+                out.append("oom")
+        for k, req in ((0, 1), (0, 1), (0, 2), (1, 3)):
+            go(k, req)
+        for t, sid in enumerate((0, 1)):
+            pool.set_last_access(0, sid, 10 + t)
+            pool.release(0, sid, True)
+        go(0, 2); go(0, 7); go(1, 8); go(0, 7)          # page 0 = {evictable, evictable, ., .}: step 4, never step 3
+        for sid, t in ((2, 3), (3, 4)):
+            pool.set_last_access(0, sid, t)
+            pool.release(0, sid, True)
+        go(1, 8)                                         # now all four are evictable: step 3
+        go(0, 9); go(0, 9)
+        pool.set_last_access(0, 6, 5)
+        pool.release(0, 6, True)
+        go(0, 10); go(0, 10)
+        return out
+    want = script(OracleCachingPool(3 * 1024, [256, 1024]))
+    got = script(LibAsOracle(opaque_pool(3, [256, 1024])))
+    assert got == want
+    assert want[5] == (2, []) and want[6] == "oom" and want[8] == (0, [(0, 0), (0, 1), (0, 2), (0, 3)])
+
+
 @pytest.mark.parametrize("seed,sizes,n_large", [(1, [256, 384], 10), (2, [64, 64], 24), (3, [2048, 3072, 6144], 8),
                                                 (4, [64, 640], 12), (5, [16384, 32768], 9)])
 def test_random_caching_traces_match_oracle(seed, sizes, n_large):
