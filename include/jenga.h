@@ -283,10 +283,13 @@ int64_t jenga_decode_workspace_bytes(const jenga_pool* pool, int32_t kind, int32
  *                from k_new / v_new, stores it into the page, and attends to it -- which saves
  *                the separate jenga_kv_append launch (for very large batches of short requests
  *                the library still runs the append as a launch of its own in front, which is
- *                faster there).  Results are identical either way.
+ *                faster there).  Pool contents and results are identical either way.
  *   block_table  device int32 [batch][bt_stride]; every page overlapping Vis_b must be
  *                resident (>= 0); other entries are never read
- *   seq_lens     device int32 [batch], each <= max_seq_len (larger ones are clamped)
+ *   seq_lens     device int32 [batch], each <= max_seq_len.  A larger one (a caller error, e.g. a
+ *                stale max_seq_len) is clamped in both kernels: the request is attended over its
+ *                first max_seq_len tokens, and its k_new / v_new rows are NOT stored (their
+ *                position lies outside what the launch was sized for)
  *   max_seq_len  host upper bound of seq_lens; sizes the grid; bt_stride * T >= max_seq_len
  *   window       0: none.  WINDOW kinds: the kind's window (a smaller positive one is allowed,
  *                0 or a larger one is INVALID: those pages are not resident).

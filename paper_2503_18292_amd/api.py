@@ -52,7 +52,9 @@ def _desc_array(kinds: Sequence[KindDesc]):
 
 
 def make_kind(type: int, dtype: int = BF16, n_layers: int = 1, n_kv_heads: int = 0, head_dim: int = 0,
-              tokens_per_page: int = 16, window: int = 0, small_page_bytes: int = 0) -> KindDesc:
+              tokens_per_page: Optional[int] = None, window: int = 0, small_page_bytes: int = 0) -> KindDesc:
+    if tokens_per_page is None:                 # an OPAQUE page is one unit; attention pages default to 16 tokens
+        tokens_per_page = 1 if type == OPAQUE else 16
     return KindDesc(type, dtype, n_layers, n_kv_heads, head_dim, tokens_per_page, window, 0,
                     small_page_bytes)
 

@@ -23,7 +23,9 @@ def hipcc() -> str:
 def command(out: str = LIB) -> list:
     return [
         hipcc(), "-O3", "-std=c++17", "-fPIC", "-shared", "--offload-arch=gfx950",
-        # packed-fp32 instructions stay off
+        # packed-fp32 instructions stay off in the device pass (checked by tests/test_build_resources.py);
+        # the x86 host pass of the same command has no such feature and says so once per function
+        # group ("not a recognized feature for this target (ignoring feature)"): harmless
         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
         "-Wall", "-Wno-unused-function",
         "-I", os.path.join(ROOT, "include"), "-I", CSRC,
@@ -39,8 +41,10 @@ def build(verbose: bool = False) -> str:
     if res.returncode != 0:
         sys.stderr.write(res.stdout + res.stderr)
         raise RuntimeError("hipcc failed")
-    if verbose and res.stderr.strip():
-        sys.stderr.write(res.stderr)
+    noise = "'-packed-fp32-ops' is not a recognized feature for this target"
+    rest = "".join(ln for ln in res.stderr.splitlines(keepends=True) if noise not in ln)
+    if verbose and rest.strip():
+        sys.stderr.write(rest)
     return LIB
 
 

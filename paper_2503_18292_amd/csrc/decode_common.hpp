@@ -65,7 +65,10 @@ __device__ __forceinline__ int units_of(int L, int window, int t_log2, int tile_
   return kSegStartUnits + ((((p_hi - p_lo) << t_log2) + (1 << tile_log2) - 1) >> tile_log2);
 }
 
-// Inclusive prefix sums of units * n_kv_heads per request into LDS, lengths next to them.
+// Inclusive prefix sums of units * n_kv_heads per request into LDS, lengths next to them: the
+// length the kernels work with is min(seq_lens[i], max_seq_len), stored negated when the clamp
+// took effect (such a request is attended over its first max_seq_len tokens, and its new row,
+// whose position lies past what the caller sized the launch for, is not stored).
 // Returns W.  All 64 lanes of the (single-wave) block take part.
 __device__ __forceinline__ int scan_requests(const int32_t* seq_lens, int batch, int max_seq_len,
                                              int window, int t_log2, int tile_log2, int n_kv_heads,
@@ -73,7 +76,8 @@ __device__ __forceinline__ int scan_requests(const int32_t* seq_lens, int batch,
   int run = 0;
   for (int c0 = 0; c0 < batch; c0 += kWave) {
     const int i = c0 + lane;
-    const int Li = i < batch ? min(seq_lens[i], max_seq_len) : 0;
+    const int raw = i < batch ? seq_lens[i] : 0;
+    const int Li = min(raw, max_seq_len);
     int incl = units_of(Li, window, t_log2, tile_log2) * n_kv_heads;
 #pragma unroll
     for (int off = 1; off < kWave; off <<= 1) {
@@ -82,7 +86,7 @@ __device__ __forceinline__ int scan_requests(const int32_t* seq_lens, int batch,
     }
     if (i < batch) {
       s_incl[i] = run + incl;
-      s_len[i] = Li;
+      s_len[i] = raw > max_seq_len ? -Li : Li;
     }
     run += __builtin_amdgcn_readlane(incl, kWave - 1);
   }

@@ -82,15 +82,17 @@ __global__ __launch_bounds__(kWave) void decode_partial_kernel(const DecodeParam
       if (tile0 == 0 && lane == 0)
         *reinterpret_cast<int2*>(p.ws_meta + seg * 2) = make_int2(int(blockIdx.x), (seg0 + units_b - 1) / C);
       // fused append: the chunk that holds the tile of the newest token (position L - 1) writes it
+      // (not for a request whose length was clamped to max_seq_len: see scan_requests)
+      const int L_enc = s_len[b];
+      const int L = abs(L_enc);
       int append_tile = -1;
-      if (p.k_new != nullptr) {
-        const int L = s_len[b];
+      if (p.k_new != nullptr && L_enc > 0) {
         int lo_tok, p_lo, p_hi;
         visible_pages(L, p.window, p.t_log2, &lo_tok, &p_lo, &p_hi);
         const int t_pos = ((L - 1) - (p_lo << p.t_log2)) >> Eng::kTileLog2;
         if (t_pos >= tile0 && t_pos < tile0 + n_tiles) append_tile = t_pos - tile0;
       }
-      Eng::run(p, lane, b, kvh, s_len[b], tile0, n_tiles, append_tile, slot, s_eng);
+      Eng::run(p, lane, b, kvh, L, tile0, n_tiles, append_tile, slot, s_eng);
     }
     x = xe;
   }
@@ -107,7 +109,8 @@ __global__ __launch_bounds__(kWave) void decode_partial_kernel(const DecodeParam
 template <int D, int NW>
 __global__ __launch_bounds__(kWave * NW) void splitk_reduce_kernel(
     const float* __restrict__ ws_acc, const float* __restrict__ ws_ml, const int32_t* __restrict__ ws_meta,
-    const int32_t* __restrict__ seq_lens, int32_t n_kv_heads, int32_t n_q_heads, float* __restrict__ out) {
+    const int32_t* __restrict__ seq_lens, int32_t max_seq_len, int32_t n_kv_heads, int32_t n_q_heads,
+    float* __restrict__ out) {
   constexpr int LPR = D / 4;              // lanes per output row
   constexpr int NG = kWave / LPR;         // lane groups: 4, 2 or 1
   constexpr int R = 8 / NG;               // records per group and step
@@ -120,7 +123,7 @@ __global__ __launch_bounds__(kWave * NW) void splitk_reduce_kernel(
   const int kvh = hq / G;
   const int g = hq - kvh * G;
   float4* dst = reinterpret_cast<float4*>(out + (int64_t(b) * n_q_heads + hq) * D) + li;
-  if (seq_lens[b] <= 0) {                 // no visible token, no record (the whole block leaves)
+  if (min(seq_lens[b], max_seq_len) <= 0) {   // no visible token, no record (the whole block leaves)
     if (gi == 0 && wave == 0) *dst = make_float4(0.f, 0.f, 0.f, 0.f);
     return;
   }
@@ -202,7 +205,7 @@ __global__ __launch_bounds__(256) void kv_append_kernel(
     char* __restrict__ layer_base, int64_t small_bytes, int32_t head_stride, int32_t v_offset,
     int32_t t_log2, int32_t n_kv_heads, int32_t row_bytes, const char* __restrict__ k_new,
     const char* __restrict__ v_new, const int32_t* __restrict__ block_table, int32_t bt_stride,
-    const int32_t* __restrict__ seq_lens, int32_t batch, int32_t max_page_id) {
+    const int32_t* __restrict__ seq_lens, int32_t batch, int32_t max_len, int32_t max_page_id) {
   const int chunks = row_bytes / 16;                       // 16-byte chunks per row
   const int64_t per_req = int64_t(n_kv_heads) * 2 * chunks;
   const int64_t idx = int64_t(blockIdx.x) * blockDim.x + threadIdx.x;
@@ -214,7 +217,7 @@ __global__ __launch_bounds__(256) void kv_append_kernel(
   const int is_v = r / chunks;
   const int c = r - is_v * chunks;
   const int L = seq_lens[b];
-  if (L <= 0) return;
+  if (L <= 0 || L > max_len) return;
   const int pos = L - 1;
   const int page = pos >> t_log2;
   if (page >= bt_stride) return;
@@ -318,7 +321,8 @@ __global__ __launch_bounds__(kWave) void stream_read_kernel(const u32x4* __restr
 template <int D>
 __global__ __launch_bounds__(kWave) void splitk_reduce_packed_kernel(
     const float* __restrict__ ws_acc, const float* __restrict__ ws_ml, const int32_t* __restrict__ ws_meta,
-    const int32_t* __restrict__ seq_lens, int32_t n_kv_heads, int32_t n_q_heads, float* __restrict__ out) {
+    const int32_t* __restrict__ seq_lens, int32_t max_seq_len, int32_t n_kv_heads, int32_t n_q_heads,
+    float* __restrict__ out) {
   constexpr int LPR = D / 4;              // lanes per output row
   constexpr int NG = kWave / LPR;         // query heads per wavefront
   const int lane = threadIdx.x;
@@ -330,7 +334,7 @@ __global__ __launch_bounds__(kWave) void splitk_reduce_packed_kernel(
   const int kvh = hq / G;
   const int g = hq - kvh * G;
   float4* dst = reinterpret_cast<float4*>(out + (int64_t(b) * n_q_heads + hq) * D) + li;
-  if (seq_lens[b] <= 0) {
+  if (min(seq_lens[b], max_seq_len) <= 0) {
     *dst = make_float4(0.f, 0.f, 0.f, 0.f);
     return;
   }
@@ -510,13 +514,10 @@ int split_ws(const Geometry& g, void* workspace, int64_t workspace_bytes, float*
   return JENGA_OK;
 }
 
-}  // namespace
-
-extern "C" {
-
-int jenga_kv_append(const jenga_pool* pool, int32_t kind, int32_t layer, const void* k_new,
-                    const void* v_new, const int32_t* block_table, int32_t bt_stride,
-                    const int32_t* seq_lens, int32_t batch, jenga_stream stream) {
+// Checks and launch of the append kernel; requests longer than max_len are left alone.
+int launch_append(const jenga_pool* pool, int32_t kind, int32_t layer, const void* k_new,
+                  const void* v_new, const int32_t* block_table, int32_t bt_stride,
+                  const int32_t* seq_lens, int32_t batch, int32_t max_len, jenga_stream stream) {
   if (!pool || kind < 0 || kind >= int32_t(pool->kinds.size())) return JENGA_ERR_INVALID;
   const jenga::Kind& k = pool->kinds[kind];
   if (k.desc.type != JENGA_FULL && k.desc.type != JENGA_WINDOW) return JENGA_ERR_INVALID;
@@ -534,8 +535,20 @@ int jenga_kv_append(const jenga_pool* pool, int32_t kind, int32_t layer, const v
                      k.small_bytes, int32_t(2 * k.desc.tokens_per_page * row_bytes),
                      int32_t(k.desc.tokens_per_page * row_bytes), k.t_log2, k.desc.n_kv_heads,
                      row_bytes, static_cast<const char*>(k_new), static_cast<const char*>(v_new),
-                     block_table, bt_stride, seq_lens, batch, int32_t(pool->n_large * k.per_large - 1));
+                     block_table, bt_stride, seq_lens, batch, max_len,
+                     int32_t(pool->n_large * k.per_large - 1));
   return hip_status();
+}
+
+}  // namespace
+
+extern "C" {
+
+int jenga_kv_append(const jenga_pool* pool, int32_t kind, int32_t layer, const void* k_new,
+                    const void* v_new, const int32_t* block_table, int32_t bt_stride,
+                    const int32_t* seq_lens, int32_t batch, jenga_stream stream) {
+  return launch_append(pool, kind, layer, k_new, v_new, block_table, bt_stride, seq_lens, batch,
+                       0x7fffffff, stream);
 }
 
 int jenga_kv_write_range(const jenga_pool* pool, int32_t kind, int32_t layer, const void* k_src,
@@ -636,7 +649,7 @@ int jenga_paged_decode_partial(const jenga_pool* pool, int32_t kind, int32_t lay
   // wavefront -- the append is cheaper as a launch of its own in front (batch 1024 with 100-600
   // tokens: +2.3 % per step; equal at 4 segments per wavefront, 1.2 % slower at 1).
   if (k_new != nullptr && segments_of(g) >= 6 * int64_t(n_part)) {
-    rc = jenga_kv_append(pool, kind, layer, k_new, v_new, block_table, bt_stride, seq_lens, batch, stream);
+    rc = launch_append(pool, kind, layer, k_new, v_new, block_table, bt_stride, seq_lens, batch, max_seq_len, stream);
     if (rc != JENGA_OK) return rc;
     p.k_new = nullptr;
     p.v_new = nullptr;
@@ -675,13 +688,13 @@ int jenga_splitk_reduce(const jenga_pool* pool, int32_t kind, int32_t n_q_heads,
 #define JENGA_LAUNCH_REDUCE(DIM)                                                                       \
   if (packed)                                                                                          \
     hipLaunchKernelGGL((splitk_reduce_packed_kernel<DIM>), pgrid, dim3(kWave), 0, st, acc, ml, meta,  \
-                       seq_lens, k.desc.n_kv_heads, n_q_heads, out);                                   \
+                       seq_lens, max_seq_len, k.desc.n_kv_heads, n_q_heads, out);                      \
   else if (wide)                                                                                       \
     hipLaunchKernelGGL((splitk_reduce_kernel<DIM, 4>), grid, dim3(4 * kWave), 0, st, acc, ml, meta,   \
-                       seq_lens, k.desc.n_kv_heads, n_q_heads, out);                                   \
+                       seq_lens, max_seq_len, k.desc.n_kv_heads, n_q_heads, out);                      \
   else                                                                                                 \
     hipLaunchKernelGGL((splitk_reduce_kernel<DIM, 1>), grid, dim3(kWave), 0, st, acc, ml, meta,       \
-                       seq_lens, k.desc.n_kv_heads, n_q_heads, out)
+                       seq_lens, max_seq_len, k.desc.n_kv_heads, n_q_heads, out)
   switch (k.desc.head_dim) {
     case 64: JENGA_LAUNCH_REDUCE(64); break;
     case 128: JENGA_LAUNCH_REDUCE(128); break;

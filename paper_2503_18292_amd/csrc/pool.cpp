@@ -42,7 +42,8 @@ int derive_kind(const jenga_kind_desc& d, Kind* k) {
     k->t_log2 = 0;
     while ((1 << k->t_log2) < d.tokens_per_page) ++k->t_log2;
   } else {
-    if (d.small_page_bytes <= 0 || d.window != 0) return JENGA_ERR_INVALID;
+    // an OPAQUE page is one unit: request lengths of such a kind count pages
+    if (d.small_page_bytes <= 0 || d.window != 0 || d.tokens_per_page != 1) return JENGA_ERR_INVALID;
     k->slice_bytes = 0;
     k->small_bytes = d.small_page_bytes;
     k->t_log2 = 0;

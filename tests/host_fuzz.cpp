@@ -31,6 +31,15 @@ int main(int argc, char** argv) {
   CHECK(jenga_lcm_page_bytes(kinds, 3, &lcm) == JENGA_OK && lcm == 48 * 1024);
   jenga_pool* pool = nullptr;
   const int64_t n_large = 40;
+  // an OPAQUE page is one unit: any other tokens_per_page (0 would divide by zero in the
+  // request layer) is refused at creation
+  for (int32_t bad_t : {0, -1, 16}) {
+    jenga_kind_desc bad[3] = {kinds[0], kinds[1], kinds[2]};
+    bad[2].tokens_per_page = bad_t;
+    int64_t l = 0;
+    CHECK(jenga_lcm_page_bytes(bad, 3, &l) == JENGA_ERR_INVALID);
+    CHECK(jenga_pool_create(nullptr, n_large * lcm, lcm, bad, 3, &pool) == JENGA_ERR_INVALID && pool == nullptr);
+  }
   CHECK(jenga_pool_create(nullptr, n_large * lcm + 100, lcm, kinds, 3, &pool) == JENGA_OK);
 
   std::vector<std::pair<int, int>> used, cached;

@@ -115,4 +115,53 @@ def test_lengths_above_max_seq_len_are_clamped():
     r.pool.paged_decode(k, layer, q, table, r.seq_lens[k], cap, 0, r.scale(k), r.workspace[k], got)
     torch.cuda.synchronize()
     assert torch.equal(got.cpu(), want.cpu())
+    # the same with the new rows handed to the decode call: a request whose length exceeds
+    # max_seq_len is attended as clamped and its rows are NOT stored (row max_seq_len - 1 holds a
+    # valid cached token); requests within the bound are appended as usual
+    k_new, v_new = r.inputs[(k, layer)][1:]
+    before = r.pool_u8.clone()
+    got2 = torch.empty_like(want)
+    r.pool.paged_decode(k, layer, q, table, r.seq_lens[k], cap, 0, r.scale(k), r.workspace[k], got2, 0, k_new, v_new)
+    torch.cuda.synchronize()
+    assert torch.equal(got2.cpu(), want.cpu())        # the row of request 1 was already in the pool: same bytes
+    assert torch.equal(r.pool_u8.cpu(), before.cpu())
+    # max_seq_len = 0 with positive lengths: nothing visible, zeros out, nothing read or stored
+    got3 = torch.full_like(want, 7.0)
+    r.pool.paged_decode(k, layer, q, table, r.seq_lens[k], 0, 0, r.scale(k), r.workspace[k], got3, 0, k_new, v_new)
+    torch.cuda.synchronize()
+    assert float(got3.abs().max()) == 0.0 and torch.equal(r.pool_u8.cpu(), before.cpu())
+    r.close()
+
+
+def test_clamped_request_is_not_appended_when_the_append_runs_in_front():
+    """Batch 1024 x 8 KV heads (the library runs the append as its own launch in front): a request
+    longer than max_seq_len is skipped by that launch exactly as by the fused path."""
+    cfg = custom_cfg("bf16", 64, 16, 8, FULL, batch=MAX_BATCH, lo=0, hi=40, n_layers=1)
+    r = _runner(cfg, 5)
+    prepare(r)
+    k, layer = r.schedule[0]
+    q, k_new, v_new = r.inputs[(k, layer)]
+    lens = r.seq_lens[k].clone()
+    cap = r.max_len[k]
+    over = [3, 500, 1023]
+    lens[over] = cap + 5                              # caller error: beyond what the launch was sized for
+    before = r.pool_u8.clone()
+    out = torch.empty_like(r.out[(k, layer)])
+    r.pool.paged_decode(k, layer, q, r.tables[k], lens, cap, 0, r.scale(k), r.workspace[k], out, 0, k_new, v_new)
+    torch.cuda.synchronize()
+    # expected pool: the separate append with the clamped requests left out
+    lens_ok = r.seq_lens[k].clone()
+    lens_ok[over] = 0
+    after = r.pool_u8.clone()
+    r.pool_u8.copy_(before)
+    r.pool.kv_append(k, layer, k_new, v_new, r.tables[k], lens_ok)
+    torch.cuda.synchronize()
+    assert torch.equal(after.cpu(), r.pool_u8.cpu())
+    # the other requests are served as ever (the partition boundaries moved, so not bit for bit)
+    ref = torch.empty_like(out)
+    r.pool.paged_decode(k, layer, q, r.tables[k], r.seq_lens[k], cap, 0, r.scale(k), r.workspace[k], ref)
+    torch.cuda.synchronize()
+    keep = torch.ones(MAX_BATCH, dtype=torch.bool)
+    keep[over] = False
+    assert torch.allclose(out.cpu()[keep], ref.cpu()[keep], atol=1e-4, rtol=0)
     r.close()

@@ -181,6 +181,10 @@ def test_error_paths():
         J.Pool(None, 4096, [make_kind(J.WINDOW, J.BF16, 1, 2, 64, 16, window=0)])
     with pytest.raises(J.JengaError):
         J.Pool(128, 4096, [K(256)])                                       # base not 256-byte aligned
+    for bad_t in (0, -3, 16):                                             # an OPAQUE page is one unit
+        with pytest.raises(J.JengaError) as e:
+            J.Pool(None, 4096, [make_kind(J.OPAQUE, tokens_per_page=bad_t, small_page_bytes=256)])
+        assert e.value.status == -1
     pool = J.Pool(None, 2 * 768, [K(256), K(384)])
     a = pool.alloc_small(0, 1)
     pool.free_small(0, a)
