@@ -39,7 +39,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="gemma2_9b",
-                    choices=["tiny", "gemma2_9b", "llama32_vision_11b", "jamba_like", "long_5to1"])
+                    choices=["tiny", "gemma2_9b", "llama32_vision_11b", "jamba_like", "long_5to1",
+                             "short_b1024", "jamba_like_literal"])
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--pages-per-split", type=int, default=0, help="0: library's choice")
     ap.add_argument("--no-kernel-events", action="store_true",

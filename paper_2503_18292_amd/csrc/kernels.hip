@@ -503,14 +503,26 @@ int64_t workspace_bytes_for(const Geometry& g) {
 
 int hip_status() { return hipGetLastError() == hipSuccess ? JENGA_OK : JENGA_ERR_HIP; }
 
-int split_ws(const Geometry& g, void* workspace, int64_t workspace_bytes, float** acc, float** ml,
-             int32_t** meta) {
+struct Workspace {
+  float* acc;
+  float* ml;
+  int32_t* meta;
+};
+
+// Carves the three arrays out of `base` (the layout only depends on the geometry).
+Workspace carve_ws(const Geometry& g, void* base) {
+  Workspace ws;
+  ws.acc = static_cast<float*>(base);
+  ws.ml = ws.acc + g.slots * g.G * g.kind->desc.head_dim;
+  ws.meta = reinterpret_cast<int32_t*>(ws.ml + g.slots * g.G * 2);
+  return ws;
+}
+
+int split_ws(const Geometry& g, void* workspace, int64_t workspace_bytes, Workspace* ws) {
   if (!workspace) return JENGA_ERR_INVALID;
   if (!aligned16(workspace)) return JENGA_ERR_ALIGN;
   if (workspace_bytes < workspace_bytes_for(g)) return JENGA_ERR_WORKSPACE;
-  *acc = static_cast<float*>(workspace);
-  *ml = *acc + g.slots * g.G * g.kind->desc.head_dim;
-  *meta = reinterpret_cast<int32_t*>(*ml + g.slots * g.G * 2);
+  *ws = carve_ws(g, workspace);
   return JENGA_OK;
 }
 
@@ -537,6 +549,111 @@ int launch_append(const jenga_pool* pool, int32_t kind, int32_t layer, const voi
                      row_bytes, static_cast<const char*>(k_new), static_cast<const char*>(v_new),
                      block_table, bt_stride, seq_lens, batch, max_len,
                      int32_t(pool->n_large * k.per_large - 1));
+  return hip_status();
+}
+
+// What the host can check of the partial kernel's arguments (the geometry is already valid).
+int check_partial_args(const jenga_pool* pool, const Geometry& g, int32_t layer, const void* q,
+                       const void* k_new, const void* v_new, const int32_t* block_table,
+                       int32_t bt_stride, const int32_t* seq_lens, int32_t max_seq_len) {
+  const jenga::Kind& k = *g.kind;
+  if (!pool->base || layer < 0 || layer >= k.desc.n_layers || !q || !block_table || !seq_lens ||
+      bt_stride < 1)
+    return JENGA_ERR_INVALID;
+  if (int64_t(bt_stride) * k.desc.tokens_per_page < max_seq_len) return JENGA_ERR_INVALID;
+  if (!aligned16(q)) return JENGA_ERR_ALIGN;
+  if ((k_new == nullptr) != (v_new == nullptr)) return JENGA_ERR_INVALID;
+  if (k_new && k.desc.type != JENGA_FULL && k.desc.type != JENGA_WINDOW) return JENGA_ERR_INVALID;
+  if (k_new && (!aligned16(k_new) || !aligned16(v_new))) return JENGA_ERR_ALIGN;
+  return JENGA_OK;
+}
+
+// Launches the partial kernel (and, for large batches of short requests, the append in front of
+// it) with checked arguments; the records go to `ws`.
+int launch_partial(const jenga_pool* pool, int32_t kind, const Geometry& g, int32_t layer, const void* q,
+                   int32_t n_q_heads, const void* k_new, const void* v_new, const int32_t* block_table,
+                   int32_t bt_stride, const int32_t* seq_lens, int32_t batch, int32_t max_seq_len,
+                   int32_t window, float scale, const Workspace& ws, jenga_stream stream) {
+  if (batch == 0) return JENGA_OK;
+  const jenga::Kind& k = *g.kind;
+  const int row_bytes = k.desc.head_dim * k.elem_bytes;
+  DecodeParams p;
+  p.layer_base = pool->base + int64_t(layer) * k.slice_bytes;
+  p.small_bytes = k.small_bytes;
+  p.head_stride = 2 * k.desc.tokens_per_page * row_bytes;
+  p.v_offset = k.desc.tokens_per_page * row_bytes;
+  p.t_log2 = k.t_log2;
+  p.n_kv_heads = k.desc.n_kv_heads;
+  p.n_q_heads = n_q_heads;
+  p.group = g.G;
+  p.max_page_id = int32_t(pool->n_large * k.per_large - 1);
+  p.q = q;
+  p.block_table = block_table;
+  p.bt_stride = bt_stride;
+  p.seq_lens = seq_lens;
+  p.batch = batch;
+  p.max_seq_len = max_seq_len;
+  p.window = window;
+  p.scale_log2 = scale * 1.4426950408889634f;
+  p.chunk_tiles = g.chunk_tiles;
+  p.min_chunk_tiles = g.min_chunk_tiles;
+  p.k_new = k_new;
+  p.v_new = v_new;
+  p.ws_acc = ws.acc;
+  p.ws_ml = ws.ml;
+  p.ws_meta = ws.meta;
+  const int n_part = launch_partitions(g);
+  // Every appended row costs its wavefront the latency of a store (loads and stores share one
+  // in-order counter): with many short requests -- six or more (request, KV head) segments per
+  // wavefront -- the append is cheaper as a launch of its own in front (batch 1024 with 100-600
+  // tokens: +2.3 % per step; equal at 4 segments per wavefront, 1.2 % slower at 1).
+  if (k_new != nullptr && segments_of(g) >= 6 * int64_t(n_part)) {
+    const int rc = launch_append(pool, kind, layer, k_new, v_new, block_table, bt_stride, seq_lens, batch,
+                                 max_seq_len, stream);
+    if (rc != JENGA_OK) return rc;
+    p.k_new = nullptr;
+    p.v_new = nullptr;
+  }
+  hipLaunchKernelGGL(g.fn, dim3(unsigned(n_part)), dim3(kWave), 0, static_cast<hipStream_t>(stream), p);
+  return hip_status();
+}
+
+// Launches the reduction that merges the records in `ws` into `out`.
+int launch_reduce(const Geometry& g, int32_t n_q_heads, const int32_t* seq_lens, int32_t batch,
+                  int32_t max_seq_len, const Workspace& ws, float* out, jenga_stream stream) {
+  if (batch == 0) return JENGA_OK;
+  const jenga::Kind& k = *g.kind;
+  float* acc = ws.acc;
+  float* ml = ws.ml;
+  int32_t* meta = ws.meta;
+  const dim3 grid(static_cast<unsigned>(n_q_heads), static_cast<unsigned>(batch));
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  // Four wavefronts per (request, query head) when the segments are few enough to have more than
+  // about eight records each.
+  const bool wide = launch_partitions(g) >= 8 * segments_of(g);
+  // Many short segments (fewer than two records each on average): 256 / D query heads per
+  // wavefront.  Batch 1024 with 100-600 tokens: +1.7 % per step with 128-element heads, +8 % with
+  // 64-element heads; with two to three records per segment and some long ones (the Jamba-like
+  // workload) the one-head kernel is 0.4 % faster, hence the bound.
+  const int heads_per_wave = 256 / k.desc.head_dim;
+  const bool packed = heads_per_wave > 1 && int64_t(launch_partitions(g)) < segments_of(g);
+  const dim3 pgrid(static_cast<unsigned>((n_q_heads + heads_per_wave - 1) / heads_per_wave), static_cast<unsigned>(batch));
+#define JENGA_LAUNCH_REDUCE(DIM)                                                                       \
+  if (packed)                                                                                          \
+    hipLaunchKernelGGL((splitk_reduce_packed_kernel<DIM>), pgrid, dim3(kWave), 0, st, acc, ml, meta,  \
+                       seq_lens, max_seq_len, k.desc.n_kv_heads, n_q_heads, out);                      \
+  else if (wide)                                                                                       \
+    hipLaunchKernelGGL((splitk_reduce_kernel<DIM, 4>), grid, dim3(4 * kWave), 0, st, acc, ml, meta,   \
+                       seq_lens, max_seq_len, k.desc.n_kv_heads, n_q_heads, out);                      \
+  else                                                                                                 \
+    hipLaunchKernelGGL((splitk_reduce_kernel<DIM, 1>), grid, dim3(kWave), 0, st, acc, ml, meta,       \
+                       seq_lens, max_seq_len, k.desc.n_kv_heads, n_q_heads, out)
+  switch (k.desc.head_dim) {
+    case 64: JENGA_LAUNCH_REDUCE(64); break;
+    case 128: JENGA_LAUNCH_REDUCE(128); break;
+    default: JENGA_LAUNCH_REDUCE(256); break;
+  }
+#undef JENGA_LAUNCH_REDUCE
   return hip_status();
 }
 
@@ -602,60 +719,13 @@ int jenga_paged_decode_partial(const jenga_pool* pool, int32_t kind, int32_t lay
   Geometry g;
   int rc = decode_geometry(pool, kind, n_q_heads, batch, max_seq_len, window, pages_per_split, &g);
   if (rc != JENGA_OK) return rc;
-  const jenga::Kind& k = *g.kind;
-  if (!pool->base || layer < 0 || layer >= k.desc.n_layers || !q || !block_table || !seq_lens ||
-      bt_stride < 1)
-    return JENGA_ERR_INVALID;
-  if (int64_t(bt_stride) * k.desc.tokens_per_page < max_seq_len) return JENGA_ERR_INVALID;
-  if (!aligned16(q)) return JENGA_ERR_ALIGN;
-  if ((k_new == nullptr) != (v_new == nullptr)) return JENGA_ERR_INVALID;
-  if (k_new && k.desc.type != JENGA_FULL && k.desc.type != JENGA_WINDOW) return JENGA_ERR_INVALID;
-  if (k_new && (!aligned16(k_new) || !aligned16(v_new))) return JENGA_ERR_ALIGN;
-  float *acc = nullptr, *ml = nullptr;
-  int32_t* meta = nullptr;
-  rc = split_ws(g, workspace, workspace_bytes, &acc, &ml, &meta);
+  rc = check_partial_args(pool, g, layer, q, k_new, v_new, block_table, bt_stride, seq_lens, max_seq_len);
   if (rc != JENGA_OK) return rc;
-  if (batch == 0) return JENGA_OK;
-
-  const int row_bytes = k.desc.head_dim * k.elem_bytes;
-  DecodeParams p;
-  p.layer_base = pool->base + int64_t(layer) * k.slice_bytes;
-  p.small_bytes = k.small_bytes;
-  p.head_stride = 2 * k.desc.tokens_per_page * row_bytes;
-  p.v_offset = k.desc.tokens_per_page * row_bytes;
-  p.t_log2 = k.t_log2;
-  p.n_kv_heads = k.desc.n_kv_heads;
-  p.n_q_heads = n_q_heads;
-  p.group = g.G;
-  p.max_page_id = int32_t(pool->n_large * k.per_large - 1);
-  p.q = q;
-  p.block_table = block_table;
-  p.bt_stride = bt_stride;
-  p.seq_lens = seq_lens;
-  p.batch = batch;
-  p.max_seq_len = max_seq_len;
-  p.window = window;
-  p.scale_log2 = scale * 1.4426950408889634f;
-  p.chunk_tiles = g.chunk_tiles;
-  p.min_chunk_tiles = g.min_chunk_tiles;
-  p.k_new = k_new;
-  p.v_new = v_new;
-  p.ws_acc = acc;
-  p.ws_ml = ml;
-  p.ws_meta = meta;
-  const int n_part = launch_partitions(g);
-  // Every appended row costs its wavefront the latency of a store (loads and stores share one
-  // in-order counter): with many short requests -- six or more (request, KV head) segments per
-  // wavefront -- the append is cheaper as a launch of its own in front (batch 1024 with 100-600
-  // tokens: +2.3 % per step; equal at 4 segments per wavefront, 1.2 % slower at 1).
-  if (k_new != nullptr && segments_of(g) >= 6 * int64_t(n_part)) {
-    rc = launch_append(pool, kind, layer, k_new, v_new, block_table, bt_stride, seq_lens, batch, max_seq_len, stream);
-    if (rc != JENGA_OK) return rc;
-    p.k_new = nullptr;
-    p.v_new = nullptr;
-  }
-  hipLaunchKernelGGL(g.fn, dim3(unsigned(n_part)), dim3(kWave), 0, static_cast<hipStream_t>(stream), p);
-  return hip_status();
+  Workspace ws;
+  rc = split_ws(g, workspace, workspace_bytes, &ws);
+  if (rc != JENGA_OK) return rc;
+  return launch_partial(pool, kind, g, layer, q, n_q_heads, k_new, v_new, block_table, bt_stride, seq_lens,
+                        batch, max_seq_len, window, scale, ws, stream);
 }
 
 int jenga_splitk_reduce(const jenga_pool* pool, int32_t kind, int32_t n_q_heads,
@@ -665,43 +735,12 @@ int jenga_splitk_reduce(const jenga_pool* pool, int32_t kind, int32_t n_q_heads,
   Geometry g;
   int rc = decode_geometry(pool, kind, n_q_heads, batch, max_seq_len, window, pages_per_split, &g);
   if (rc != JENGA_OK) return rc;
-  const jenga::Kind& k = *g.kind;
   if (!seq_lens || !out) return JENGA_ERR_INVALID;
   if (!aligned16(out)) return JENGA_ERR_ALIGN;
-  float *acc = nullptr, *ml = nullptr;
-  int32_t* meta = nullptr;
-  rc = split_ws(g, const_cast<void*>(workspace), workspace_bytes, &acc, &ml, &meta);
+  Workspace ws;
+  rc = split_ws(g, const_cast<void*>(workspace), workspace_bytes, &ws);
   if (rc != JENGA_OK) return rc;
-  if (batch == 0) return JENGA_OK;
-  const dim3 grid(static_cast<unsigned>(n_q_heads), static_cast<unsigned>(batch));
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  // Four wavefronts per (request, query head) when the segments are few enough to have more than
-  // about eight records each.
-  const bool wide = launch_partitions(g) >= 8 * segments_of(g);
-  // Many short segments (fewer than two records each on average): 256 / D query heads per
-  // wavefront.  Batch 1024 with 100-600 tokens: +1.7 % per step with 128-element heads, +8 % with
-  // 64-element heads; with two to three records per segment and some long ones (the Jamba-like
-  // workload) the one-head kernel is 0.4 % faster, hence the bound.
-  const int heads_per_wave = 256 / k.desc.head_dim;
-  const bool packed = heads_per_wave > 1 && int64_t(launch_partitions(g)) < segments_of(g);
-  const dim3 pgrid(static_cast<unsigned>((n_q_heads + heads_per_wave - 1) / heads_per_wave), static_cast<unsigned>(batch));
-#define JENGA_LAUNCH_REDUCE(DIM)                                                                       \
-  if (packed)                                                                                          \
-    hipLaunchKernelGGL((splitk_reduce_packed_kernel<DIM>), pgrid, dim3(kWave), 0, st, acc, ml, meta,  \
-                       seq_lens, max_seq_len, k.desc.n_kv_heads, n_q_heads, out);                      \
-  else if (wide)                                                                                       \
-    hipLaunchKernelGGL((splitk_reduce_kernel<DIM, 4>), grid, dim3(4 * kWave), 0, st, acc, ml, meta,   \
-                       seq_lens, max_seq_len, k.desc.n_kv_heads, n_q_heads, out);                      \
-  else                                                                                                 \
-    hipLaunchKernelGGL((splitk_reduce_kernel<DIM, 1>), grid, dim3(kWave), 0, st, acc, ml, meta,       \
-                       seq_lens, max_seq_len, k.desc.n_kv_heads, n_q_heads, out)
-  switch (k.desc.head_dim) {
-    case 64: JENGA_LAUNCH_REDUCE(64); break;
-    case 128: JENGA_LAUNCH_REDUCE(128); break;
-    default: JENGA_LAUNCH_REDUCE(256); break;
-  }
-#undef JENGA_LAUNCH_REDUCE
-  return hip_status();
+  return launch_reduce(g, n_q_heads, seq_lens, batch, max_seq_len, ws, out, stream);
 }
 
 int jenga_paged_decode(const jenga_pool* pool, int32_t kind, int32_t layer, const void* q,

@@ -15,7 +15,8 @@ from workloads.configs import CROSS
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("name", ["gemma2_9b", "llama32_vision_11b", "jamba_like", "long_5to1"])
+@pytest.mark.parametrize("name", ["gemma2_9b", "llama32_vision_11b", "jamba_like", "long_5to1", "short_b1024",
+                                  "jamba_like_literal"])
 def test_full_size_sampled_parity(name):
     from paper_2503_18292_amd.runner import DecodeRunner
     print(f"[case] full size {name}", flush=True)
@@ -59,6 +60,9 @@ def test_full_size_sampled_parity(name):
                 err = np.abs(got[b] - want)
                 rel = np.linalg.norm(got[b] - want) / max(np.linalg.norm(want), 1e-30)
                 assert err.max() <= 2e-2 and rel <= 1e-2, f"{name} kind {k} layer {layer} request {b}: {err.max()} {rel}"
+                # regression bound next to the stated tolerance: with hundreds to thousands of visible
+                # tokens the result is an average, and the kernels reach about 1e-6 here
+                assert err.max() <= 1e-5, f"{name} kind {k} layer {layer} request {b}: {err.max()} above the regression bound"
                 worst_abs, worst_rel = max(worst_abs, float(err.max())), max(worst_rel, float(rel))
     print(f"  worst abs {worst_abs:.2e} rel {worst_rel:.2e}", flush=True)
     r.close()

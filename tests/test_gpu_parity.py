@@ -3,7 +3,12 @@
 Every case prefills the pool with NaN bytes and scatters NaN into token rows outside the
 visible set, so each parity check is also a check that nothing outside the visible set is
 read into the result.  Tolerances are the ones stated for this build: max abs 1e-5 for
-fp32 K/V; for bf16 K/V max abs 2e-2 and relative (norm-wise) 1e-2.
+fp32 K/V; for bf16 K/V max abs 2e-2 and relative (norm-wise) 1e-2.  Next to them stands a
+regression bound at what the kernels reach with a margin: the bf16 path multiplies bf16 inputs
+exactly, accumulates in fp32 and feeds the probabilities to the value product as the sum of two
+bf16 numbers, so its results lie within a few 1e-6 of the oracle on unit-variance inputs; the
+bound of 1e-4 (element by element) catches the loss of the second term (4e-3 on short requests,
+tests/test_accuracy_model.py) or a wrong rescale, which the stated 2e-2 would let through.
 """
 import math
 
@@ -20,6 +25,7 @@ pytestmark = pytest.mark.gpu
 TOL_F32_ABS = 1e-5
 TOL_BF16_ABS = 2e-2
 TOL_BF16_REL = 1e-2
+REG_BF16_ABS = 1e-4       # regression bound, element-wise, for inputs of standard deviation <= 1
 
 
 def _runner(cfg, seed, **kw):
@@ -65,6 +71,8 @@ def check_against_oracle(r, label=""):
                 assert err.max() <= TOL_BF16_ABS, f"{label} kind {k} layer {layer} req {b}: {err.max()}"
                 rel = np.linalg.norm(got[b] - want) / max(np.linalg.norm(want), 1e-30)
                 assert rel <= TOL_BF16_REL, f"{label} kind {k} layer {layer} req {b}: rel {rel}"
+                reg = REG_BF16_ABS * max(1.0, r.cfg.value_sigma)
+                assert err.max() <= reg, f"{label} kind {k} layer {layer} req {b}: {err.max()} above the regression bound {reg}"
             worst = max(worst, float(err.max()))
     return worst
 
@@ -230,6 +238,36 @@ def test_edge_lengths(ctx):
         r.close()
 
 
+def score_rounding_envelope(q, K, V, scale, window, dtype):
+    """Element-wise bound [H_q, D] on |result - oracle| for arithmetic that holds each score as an
+    fp32 number in the base-2 domain, derived from the oracle's own quantities in fp64.
+
+    Rounding a score s2 = s * log2(e) to fp32 moves it by up to u2 = ulp_fp32(s2) / 2, i.e. the
+    natural score by u = u2 * ln 2.  With p = softmax(s) and out = p @ V,
+    d out[d] / d s[t] = p[t] * (V[t, d] - out[d]), so every sign pattern of the perturbations stays
+    inside  env[d] = sum_t p[t] * |V[t, d] - out[d]| * u[t]  to first order (u <= 3e-5 here).  The
+    bound is 2 * env (the dot product, the multiplication by the scale and the subtraction of the
+    running maximum each round once) plus the rounding of the weighted sum itself:
+    4 * 2^-24 * sum_t p[t] |V[t, d]| for an fp32 accumulation, and for bf16 K/V 2^-16 times the
+    same sum for the probabilities entering the value product with 16 significant bits."""
+    q, K, V = (np.asarray(x, dtype=np.float64) for x in (q, K, V))
+    Hq, Hkv = q.shape[0], K.shape[0]
+    G = Hq // Hkv
+    lo, hi = visible_range(K.shape[1], window)
+    bound = np.zeros_like(q)
+    for h in range(Hq):
+        Kh, Vh = K[h // G, lo:hi], V[h // G, lo:hi]
+        s = scale * (Kh @ q[h])
+        p = np.exp(s - s.max())
+        p /= p.sum()
+        out = p @ Vh
+        u = np.spacing(np.abs(s * math.log2(math.e)).astype(np.float32)).astype(np.float64) / 2 * math.log(2.0)
+        env = (p * u) @ np.abs(Vh - out)
+        acc = p @ np.abs(Vh)
+        bound[h] = 2 * env + (4 * 2.0 ** -24 + (2.0 ** -16 if dtype == "bf16" else 0.0)) * acc
+    return bound
+
+
 @pytest.mark.parametrize("dtype,D,G,T", [("bf16", 128, 4, 16), ("bf16", 256, 2, 16), ("f32", 64, 2, 16), ("bf16", 64, 8, 32),
                                          ("f32", 128, 8, 16)])
 def test_peaked_softmax_large_scores(dtype, D, G, T):
@@ -242,6 +280,7 @@ def test_peaked_softmax_large_scores(dtype, D, G, T):
     prepare(r)
     r.device_step()
     torch.cuda.synchronize()
+    worst_rel = 0.0
     for k, layer in r.schedule:
         kd = r.cfg.kinds[k]
         q = r.inputs[(k, layer)][0].cpu().double().numpy()
@@ -250,13 +289,16 @@ def test_peaked_softmax_large_scores(dtype, D, G, T):
             K, V = r.contiguous_kv(k, layer, b)
             want = decode_attention_one(q[b], K.double().numpy(), V.double().numpy(), r.scale(k), 0)
             assert np.isfinite(got[b]).all()
-            # outputs are of the magnitude of V here: relative tolerance only.  fp32: a score of
-            # magnitude 2^9 .. 2^10 in the base-2 domain has a spacing of 2^-14 = 6.1e-5, so a weight
-            # exp2(s - m) carries a relative error of up to half that times ln 2 = 2.1e-5 from the
-            # rounding of the score alone, whatever the order of the summation; 4e-5 leaves a factor
-            # of two for the accumulation.
+            # Outputs are of the magnitude of V here (150), and the scores of several hundred are
+            # held in fp32 by any implementation of this path: the bound is what that rounding
+            # allows, computed from the oracle (see score_rounding_envelope), not a constant.
+            bound = score_rounding_envelope(q[b], K.double().numpy(), V.double().numpy(), r.scale(k), 0, dtype)
+            excess = np.abs(got[b] - want) - bound
+            assert excess.max() <= 0, f"kind {k} layer {layer} req {b}: {np.abs(got[b] - want).max()} vs bound {bound.max()}"
             rel = np.linalg.norm(got[b] - want) / np.linalg.norm(want)
-            assert rel <= (4e-5 if dtype == "f32" else TOL_BF16_REL), rel
+            worst_rel = max(worst_rel, rel)
+            assert rel <= (1e-4 if dtype == "f32" else TOL_BF16_REL), rel
+    print(f"  worst norm-wise rel err {worst_rel:.2e}", flush=True)
     r.close()
 
 
@@ -440,7 +482,7 @@ def test_bad_table_entries_are_clamped_not_followed():
         for b in (0, 3):
             K, V = r.contiguous_kv(0, 0, b)
             want = decode_attention_one(q[b], K.double().numpy(), V.double().numpy(), r.scale(0), 0)
-            assert np.abs(got[b] - want).max() <= TOL_BF16_ABS
+            assert np.abs(got[b] - want).max() <= REG_BF16_ABS
         # nothing was written for the two requests with bad tables: only requests 0 and 3 appended
         changed = (r.pool_u8 != before).sum().item()
         assert changed <= 2 * 2 * 2 * 128 * 2

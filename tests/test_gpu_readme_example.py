@@ -34,5 +34,5 @@ def test_readme_example_runs_and_is_right():
                              k_new=env["k_new"], v_new=env["v_new"])
     torch.cuda.synchronize()
     want = decode_attention_one(q[1].cpu().double().numpy(), K.double().numpy(), V.double().numpy(), 256 ** -0.5, 0)
-    assert np.abs(out[1].cpu().double().numpy() - want).max() <= 2e-2
+    assert np.abs(out[1].cpu().double().numpy() - want).max() <= 1e-4      # stated tolerance 2e-2; the kernels reach 1e-6
     env["pool"].destroy()

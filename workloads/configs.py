@@ -153,12 +153,31 @@ def long_5to1() -> ModelCfg:
     )
 
 
+def short_b1024() -> ModelCfg:
+    """Many short requests: the regime a larger decode batch (what the paper's memory savings buy,
+    Sec. 7.3) pushes the kernel into.  A homogeneous Llama-3.1-8B-shaped model (32 full-attention
+    layers, 32 query and 8 KV heads of 128 elements; Table 1 lists Llama 3.1 as the homogeneous
+    control), batch 1024, 100 to 600 cached tokens per request."""
+    return ModelCfg(
+        name="short_b1024",
+        kinds=[KindCfg("full", FULL, "bf16", 32, 32, 8, 128, 16)],
+        batch=1024, ctx=LengthDist("uniform", 100, 600),
+        build_chunk=128,
+    )
+
+
+def jamba_like_literal() -> ModelCfg:
+    return jamba_like(literal=True)
+
+
 ALL = {
     "tiny": tiny,
     "gemma2_9b": gemma2_9b,
     "llama32_vision_11b": llama32_vision_11b,
     "jamba_like": jamba_like,
     "long_5to1": long_5to1,
+    "short_b1024": short_b1024,
+    "jamba_like_literal": jamba_like_literal,
 }
 
 
