@@ -50,8 +50,8 @@ class DecodeRunner:
         self.descs = kind_descs(cfg)
         self.large_bytes = api.lcm_page_bytes(self.descs)
         n_large = cfg.pool_large_pages
-        if n_large is None:
-            n_large = scripts.pool_large_pages_needed(cfg, self.ctx, self.large_bytes)
+        if n_large is None:       # room for the contexts and for the decode steps still to come
+            n_large = scripts.pool_large_pages_needed(cfg, self.ctx + step_budget, self.large_bytes)
         self.n_large = n_large
         if pool_u8 is None:
             pool_u8 = torch.empty(n_large * self.large_bytes, dtype=torch.uint8, device=self.device)
