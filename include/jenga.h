@@ -322,6 +322,30 @@ int jenga_splitk_reduce(const jenga_pool* pool, int32_t kind, int32_t n_q_heads,
                         const void* workspace, int64_t workspace_bytes,
                         float* out, jenga_stream stream);
 
+#define JENGA_STATIC_SCRATCH_BYTES (32 * 1024 * 1024)
+/* For callers that cannot allocate device memory -- code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc: jenga_paged_decode without the workspace arguments.
+ * The records between the two kernels live in a buffer inside the library (a file-scope device
+ * array of JENGA_STATIC_SCRATCH_BYTES = 32 MiB, which every GPU the library runs on holds
+ * until the process ends); the call allocates and frees nothing, on the device or through any
+ * allocating library routine.  Arguments, checks and results are those of jenga_paged_decode
+ * (bit-identical output for pages_per_split = 0 and for any other value).
+ * Limit: JENGA_ERR_WORKSPACE when the records of this launch need more than the buffer:
+ *   (partitions + batch * n_kv_heads) * G * (head_dim + 2) * 4 + batch * n_kv_heads * 8  bytes,
+ * partitions = wavefronts the device holds at once, 1024 on an MI355X (e.g. batch 1024 with 8 KV
+ * heads, G = 4, head_dim 128 needs 19.2 MB; the Gemma-2-9B shape at batch 64 3.2 MB).
+ * Every call on one GPU uses that GPU's buffer: calls that may overlap on one GPU (different
+ * streams, or graphs replayed concurrently) race and must be serialised by the caller.  Nothing
+ * in the buffer has to start at zero; each call overwrites what it reads.
+ * Further errors: HIP (no current device, or the buffer's address cannot be found). */
+int jenga_paged_decode_static(const jenga_pool* pool, int32_t kind, int32_t layer,
+                              const void* q, int32_t n_q_heads,
+                              const void* k_new, const void* v_new,
+                              const int32_t* block_table, int32_t bt_stride,
+                              const int32_t* seq_lens, int32_t batch, int32_t max_seq_len,
+                              int32_t window, float scale, int32_t pages_per_split,
+                              float* out, jenga_stream stream);
+
 /* Measurement aids (not on the hot path): a plain device copy and a plain device read of
  * `bytes` (multiple of 16) with 16-byte accesses, used to find the achievable HBM rate and
  * to calibrate profiler byte counters.  `sink`: device, >= 4 bytes. */

@@ -73,6 +73,8 @@ SIGNATURES = {
                                              c_i32, c_i32, c_i32, c_f32, c_i32, c_vp, c_i64, c_vp]),
     "jenga_splitk_reduce": (C.c_int, [c_vp, c_i32, c_i32, c_vp, c_i32, c_i32, c_i32, c_i32, c_vp,
                                       c_i64, c_vp, c_vp]),
+    "jenga_paged_decode_static": (C.c_int, [c_vp, c_i32, c_i32, c_vp, c_i32, c_vp, c_vp, c_vp, c_i32, c_vp, c_i32,
+                                            c_i32, c_i32, c_f32, c_i32, c_vp, c_vp]),
     "jenga_stream_copy": (C.c_int, [c_vp, c_vp, c_i64, c_vp]),
     "jenga_stream_read": (C.c_int, [c_vp, c_i64, c_vp, c_vp]),
     "jenga_strerror": (C.c_char_p, [C.c_int]),

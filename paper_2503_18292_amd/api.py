@@ -291,6 +291,16 @@ class Pool:
             _ptr(workspace), workspace.numel() * workspace.element_size(), _ptr(out), _stream()),
             "jenga_paged_decode")
 
+    def paged_decode_static(self, kind: int, layer: int, q, block_table, seq_lens, max_seq_len: int,
+                            window: int, scale: float, out, pages_per_split: int = 0,
+                            k_new=None, v_new=None) -> None:
+        """jenga_paged_decode with the library's own scratch buffer: allocates nothing."""
+        _check(self._lib.jenga_paged_decode_static(
+            self._h, kind, layer, _ptr(q), q.shape[1], _ptr(k_new), _ptr(v_new),
+            _ptr(block_table), block_table.shape[1],
+            _ptr(seq_lens), seq_lens.shape[0], max_seq_len, window, scale, pages_per_split,
+            _ptr(out), _stream()), "jenga_paged_decode_static")
+
     def paged_decode_partial(self, kind: int, layer: int, q, block_table, seq_lens, max_seq_len: int,
                              window: int, scale: float, workspace, pages_per_split: int = 0,
                              k_new=None, v_new=None) -> None:

@@ -40,7 +40,6 @@
 #include <algorithm>
 #include <cstdint>
 #include <mutex>
-#include <unordered_map>
 
 #include "pool_internal.hpp"
 #include "decode_common.hpp"
@@ -370,6 +369,42 @@ __global__ __launch_bounds__(kWave) void splitk_reduce_packed_kernel(
   *dst = make_float4(acc.x * inv, acc.y * inv, acc.z * inv, acc.w * inv);
 }
 
+// ---- split-K scratch for callers that cannot allocate ------------------------------------
+//
+// jenga_paged_decode_static keeps the records between its two kernels here instead of in a
+// caller-owned workspace.  Every device the library runs on holds its own copy of the array for
+// the life of the process; host code never uses the array's name as an address (on the host it is
+// only a stand-in for the symbol) but the device address hipGetSymbolAddress reports, looked up
+// once per device with that device current.
+constexpr int64_t kStaticScratchBytes = JENGA_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of `scratch` on the current device, or nullptr (with *rc set) on failure.
+void* static_scratch(int* rc) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+    (void)hipGetLastError();
+    *rc = JENGA_ERR_HIP;
+    return nullptr;
+  }
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) {
+      (void)hipGetLastError();
+      *rc = JENGA_ERR_HIP;
+      return nullptr;
+    }
+    g_scratch_ptr[dev] = ptr;
+  }
+  *rc = JENGA_OK;
+  return g_scratch_ptr[dev];
+}
+
 // ---- host side: validation, partition geometry, launch --------------------------------
 
 using DecodeFn = void (*)(DecodeParams);
@@ -404,32 +439,32 @@ DecodeFn pick_d(int D, bool half_pages, int G) {
 }
 
 // Partitions of the automatic mode: resident blocks of `fn`, at most one per SIMD, a multiple
-// of 8 (one share per XCD), capped at kMaxPartitions.  Cached per kernel; 2048 when no device can be asked.
+// of 8 (one share per XCD), capped at kMaxPartitions.  Remembered per kernel in a fixed table (no
+// heap allocation on any call); 2048 when no device can be asked.
 int resident_partitions(DecodeFn fn) noexcept {
-  int n = 2048;
-  try {
-    static std::mutex mu;
-    static std::unordered_map<const void*, int> cache;
-    std::lock_guard<std::mutex> lock(mu);
-    auto it = cache.find(reinterpret_cast<const void*>(fn));
-    if (it != cache.end()) return it->second;
-    int dev = 0, cus = 0, per_cu = 0;
-    if (hipGetDevice(&dev) == hipSuccess &&
-        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess &&
-        hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kWave, 0) == hipSuccess &&
-        cus > 0 && per_cu > 0) {
-      // one wavefront per SIMD (4 per compute unit): measured faster than filling every slot,
-      // and it leaves each wavefront the registers for a deep load pipeline
-      n = std::min(kMaxPartitions, cus * std::min(per_cu, 4)) / 8 * 8;
-      n = std::max(n, 8);
-      cache.emplace(reinterpret_cast<const void*>(fn), n);
-    } else {
-      (void)hipGetLastError();      // no device: do not leave a sticky error, do not cache
-    }
-  } catch (...) {
-    // out of host memory while caching: the value is still right, it is just not remembered
+  constexpr unsigned kSlots = 1024;                 // far more than there are decode kernels
+  struct Entry { const void* fn; int n; };
+  static std::mutex mu;
+  static Entry table[kSlots] = {};
+  const void* key = reinterpret_cast<const void*>(fn);
+  std::lock_guard<std::mutex> lock(mu);
+  unsigned i = unsigned((reinterpret_cast<uintptr_t>(key) >> 4) * 2654435761u) % kSlots;
+  for (unsigned probes = 0; probes < kSlots && table[i].fn != nullptr; ++probes, i = (i + 1) % kSlots)
+    if (table[i].fn == key) return table[i].n;
+  int dev = 0, cus = 0, per_cu = 0;
+  if (hipGetDevice(&dev) == hipSuccess &&
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess &&
+      hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, kWave, 0) == hipSuccess &&
+      cus > 0 && per_cu > 0) {
+    // one wavefront per SIMD (4 per compute unit): measured faster than filling every slot,
+    // and it leaves each wavefront the registers for a deep load pipeline
+    int n = std::min(kMaxPartitions, cus * std::min(per_cu, 4)) / 8 * 8;
+    n = std::max(n, 8);
+    if (table[i].fn == nullptr) table[i] = Entry{key, n};
+    return n;
   }
-  return n;
+  (void)hipGetLastError();      // no device: do not leave a sticky error, do not remember
+  return 2048;
 }
 
 struct Geometry {
@@ -757,6 +792,35 @@ int jenga_paged_decode(const jenga_pool* pool, int32_t kind, int32_t layer, cons
   if (rc != JENGA_OK) return rc;
   return jenga_splitk_reduce(pool, kind, n_q_heads, seq_lens, batch, max_seq_len, window,
                              pages_per_split, workspace, workspace_bytes, out, stream);
+}
+
+int jenga_paged_decode_static(const jenga_pool* pool, int32_t kind, int32_t layer, const void* q,
+                              int32_t n_q_heads, const void* k_new, const void* v_new,
+                              const int32_t* block_table, int32_t bt_stride,
+                              const int32_t* seq_lens, int32_t batch, int32_t max_seq_len, int32_t window,
+                              float scale, int32_t pages_per_split, float* out, jenga_stream stream) {
+  if (!out) return JENGA_ERR_INVALID;
+  if (!aligned16(out)) return JENGA_ERR_ALIGN;
+  Geometry g;
+  int rc = decode_geometry(pool, kind, n_q_heads, batch, max_seq_len, window, pages_per_split, &g);
+  if (rc != JENGA_OK) return rc;
+  rc = check_partial_args(pool, g, layer, q, k_new, v_new, block_table, bt_stride, seq_lens, max_seq_len);
+  if (rc != JENGA_OK) return rc;
+  // A caller-owned workspace is sized for the largest grid the automatic mode may ever use; here
+  // the grid is known, so the records need room for exactly its partitions.
+  if (g.chunk_tiles == 0) {
+    const int64_t segs = segments_of(g);
+    g.n_part_bound = launch_partitions(g);
+    g.slots = int64_t(g.n_part_bound) + segs;
+  }
+  if (workspace_bytes_for(g) > kStaticScratchBytes) return JENGA_ERR_WORKSPACE;
+  void* base = static_scratch(&rc);
+  if (!base) return rc;
+  const Workspace ws = carve_ws(g, base);
+  rc = launch_partial(pool, kind, g, layer, q, n_q_heads, k_new, v_new, block_table, bt_stride, seq_lens,
+                      batch, max_seq_len, window, scale, ws, stream);
+  if (rc != JENGA_OK) return rc;
+  return launch_reduce(g, n_q_heads, seq_lens, batch, max_seq_len, ws, out, stream);
 }
 
 int jenga_stream_copy(void* dst, const void* src, int64_t bytes, jenga_stream stream) {
