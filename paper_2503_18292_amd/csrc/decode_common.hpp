@@ -73,25 +73,63 @@ __device__ __forceinline__ int units_of(int L, int window, int t_log2, int tile_
 __device__ __forceinline__ int scan_requests(const int32_t* seq_lens, int batch, int max_seq_len,
                                              int window, int t_log2, int tile_log2, int n_kv_heads,
                                              int lane, int* s_incl, int* s_len) {
-  int run = 0;
-  for (int c0 = 0; c0 < batch; c0 += kWave) {
-    const int i = c0 + lane;
-    const int raw = i < batch ? seq_lens[i] : 0;
+  constexpr int kRounds = kMaxBatch / kWave;
+  auto units = [&](int raw, int* enc) {
     const int Li = min(raw, max_seq_len);
-    int incl = units_of(Li, window, t_log2, tile_log2) * n_kv_heads;
+    *enc = raw > max_seq_len ? -Li : Li;
+    return units_of(Li, window, t_log2, tile_log2) * n_kv_heads;
+  };
+  if (batch <= kWave) {                        // one round: one load, one wave scan
+    const int raw = lane < batch ? seq_lens[lane] : 0;
+    int enc;
+    int incl = units(raw, &enc);
 #pragma unroll
     for (int off = 1; off < kWave; off <<= 1) {
       const int up = __shfl_up(incl, off);
       if (lane >= off) incl += up;
     }
-    if (i < batch) {
-      s_incl[i] = run + incl;
-      s_len[i] = raw > max_seq_len ? -Li : Li;
+    if (lane < batch) {
+      s_incl[lane] = incl;
+      s_len[lane] = enc;
     }
-    run += __builtin_amdgcn_readlane(incl, kWave - 1);
+    __syncthreads();
+    return __builtin_amdgcn_readlane(incl, kWave - 1);
+  }
+  // Larger batches: lane l takes the K = ceil(batch / 64) consecutive requests l*K .. l*K + K - 1.
+  // All their lengths are requested before any is used (one memory round trip instead of one per
+  // 64 requests: 7.5 us -> 1.6 us at batch 1024), each lane sums its own, one wave scan of the
+  // lane totals follows.
+  const int K = (batch + kWave - 1) / kWave;
+  int raw[kRounds];
+#pragma unroll
+  for (int r = 0; r < kRounds; ++r) {
+    const int i = lane * K + r;
+    raw[r] = (r < K && i < batch) ? seq_lens[i] : 0;
+  }
+  int own[kRounds], enc[kRounds];
+  int total = 0;
+#pragma unroll
+  for (int r = 0; r < kRounds; ++r) {
+    total += units(raw[r], &enc[r]);
+    own[r] = total;
+  }
+  int incl = total;
+#pragma unroll
+  for (int off = 1; off < kWave; off <<= 1) {
+    const int up = __shfl_up(incl, off);
+    if (lane >= off) incl += up;
+  }
+  const int before = incl - total;
+#pragma unroll
+  for (int r = 0; r < kRounds; ++r) {
+    const int i = lane * K + r;
+    if (r < K && i < batch) {
+      s_incl[i] = before + own[r];
+      s_len[i] = enc[r];
+    }
   }
   __syncthreads();
-  return run;
+  return __builtin_amdgcn_readlane(incl, kWave - 1);
 }
 
 __device__ __forceinline__ int chunk_of(int chunk_tiles, int min_chunk_tiles, int W, int n_part) {
@@ -133,8 +171,9 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));   // 16 bytes; a nat
 // the K and V requests of a tile enter run c of 64 pages, the register of run c+1 (== that of
 // run c-1, which they have just left) is reloaded.
 struct PageIds {
-  const int32_t* row;   // block-table entry of relative page 0
+  const int32_t* row;   // block-table entry of relative page 0 (nullptr: nothing loaded yet)
   int n_pages;
+  int n_loaded;         // pages the registers were loaded for (0 once a refill has replaced them)
   int lane;
   int max_id;
   int reg0, reg1;       // two scalars, not an array: an indexed member would live in scratch memory
@@ -145,8 +184,17 @@ struct PageIds {
     const int i = first + lane;
     return i < n_pages ? min(max(row[i], 0), max_id) : 0;
   }
+  // The next (request, KV head) segment of a wavefront is usually the next head of the same
+  // request, whose pages are the same ones: when the registers still hold the first 128 entries
+  // of that very row, nothing is fetched (a segment start otherwise waits a memory round trip for
+  // its page ids before it can request any K/V).
   __device__ __forceinline__ void init(const int32_t* r, int n, int l, int max_page_id) {
+    if (r == row && n <= n_loaded) {
+      n_pages = n;
+      return;
+    }
     row = r; n_pages = n; lane = l; max_id = max_page_id;
+    n_loaded = n;
     reg0 = fetch(0);
     reg1 = fetch(kWave);
   }
@@ -156,10 +204,11 @@ struct PageIds {
   }
   // Call after the K stream has issued the loads of a tile starting at page_rel.
   __device__ __forceinline__ void k_stream_at(int page_rel) {
-    if ((page_rel & (kWave - 1)) == 0 && page_rel > 0) {
+    if ((page_rel & (kWave - 1)) == 0 && page_rel > 0 && page_rel + kWave < n_pages) {
       const int next = fetch(page_rel + kWave);
       if (page_rel & kWave) reg0 = next;
       else reg1 = next;
+      n_loaded = 0;       // the registers no longer hold the start of the row
     }
   }
 };

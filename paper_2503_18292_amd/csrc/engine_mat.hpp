@@ -66,6 +66,12 @@ struct MatEngine {
   static constexpr int LROW = ROW + (F32K ? 16 : 32);
   static constexpr int kTileLog2 = PPT == 1 ? 4 : PPT == 2 ? 5 : 6;
   static constexpr int kLdsFloats = PPT * T * LROW / 4;
+  static constexpr int kG = G_;
+  // LDS left for finished records when four blocks share a compute unit's 160 KiB: 38 KiB (two
+  // are left to the allocation granularity) less the front end's two arrays of 4 KiB, this
+  // engine's V tile and 256 bytes of bookkeeping
+  static constexpr int kRecFloats = (38 * 1024 - 2 * 4 * kMaxBatch - 4 * kLdsFloats - 256) / 4;
+  static_assert(kRecFloats > 0, "LDS budget");
   static_assert(KCH == 2 || KCH == 4 || KCH == 8 || KCH == 16, "row size");
 
   typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -92,7 +98,7 @@ struct MatEngine {
   }
 
   __device__ __forceinline__ static void run(const DecodeParams& p, int lane, int b, int kvh, int L, int tile0,
-                             int n_tiles, int append_tile, int64_t slot, float* lds) {
+                             int n_tiles, int append_tile, int64_t slot, float* rec, PageIds& ids, float* lds) {
     // A 16-token block is the unit of both products.  Pages of 16, 32, 64 or 128 tokens hold 1, 2,
     // 4 or 8 blocks: block q (counted from the first visible page) lies in page q >> sh at row
     // (q & sub_mask) * 16.  An 8-token page is half a block: a block takes its rows 0..7 from one
@@ -112,7 +118,6 @@ struct MatEngine {
     const int tok0 = (p_lo << p.t_log2) + blk0 * T;
     char* v_lds = reinterpret_cast<char*>(lds);
 
-    PageIds ids;
     ids.init(p.block_table + int64_t(b) * p.bt_stride + page0, n_pages, lane, p.max_page_id);
 
     const int n = lane & 15, j = lane >> 4;
@@ -378,17 +383,33 @@ struct MatEngine {
     }
 
     l = across_groups_sum(l);
-    // one partial record: lane (n, j) holds element 16 * blk + n of heads 4j .. 4j+3
+    // one partial record: lane (n, j) holds element 16 * blk + n of heads 4j .. 4j+3.  It goes to
+    // the LDS buffer `rec` ([G][D] accumulators, then G (max, sum) pairs; the front end stores the
+    // buffered records when the wavefront is done), or straight to workspace slot `slot` when
+    // the record is too large to be buffered.
+    if (rec != nullptr) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int h = 4 * j + i;
-      if (h < G) {
-        float* dst = p.ws_acc + (slot * G + h) * D + n;
+      for (int i = 0; i < 4; ++i) {
+        const int h = 4 * j + i;
+        if (h < G) {
+          float* dst = rec + h * D + n;
 #pragma unroll
-        for (int blk = 0; blk < NBLK; ++blk) dst[blk * 16] = acc[blk][i];
+          for (int blk = 0; blk < NBLK; ++blk) dst[blk * 16] = acc[blk][i];
+        }
       }
+      if (j == 0 && n < G) *reinterpret_cast<float2*>(rec + G * D + 2 * n) = make_float2(m, l);
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int h = 4 * j + i;
+        if (h < G) {
+          float* dst = p.ws_acc + (slot * G + h) * D + n;
+#pragma unroll
+          for (int blk = 0; blk < NBLK; ++blk) dst[blk * 16] = acc[blk][i];
+        }
+      }
+      if (j == 0 && n < G) *reinterpret_cast<float2*>(p.ws_ml + (slot * G + n) * 2) = make_float2(m, l);
     }
-    if (j == 0 && n < G) *reinterpret_cast<float2*>(p.ws_ml + (slot * G + n) * 2) = make_float2(m, l);
   }
 };
 
