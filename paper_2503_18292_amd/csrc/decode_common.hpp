@@ -45,6 +45,8 @@ struct DecodeParams {
   float* ws_acc;              // [slot][G][D]
   float* ws_ml;               // [slot][G][2]  (running max, running sum)
   int32_t* ws_meta;           // [segment][2]  first and last chunk that hold tiles of the segment
+  float* out;                 // [batch][n_q_heads][D] when the reduction of the same call follows, else NULL:
+                              // a record that covers its whole segment is then written there, normalised
 };
 
 // Visible pages [p_lo, p_hi) and first visible token of a request of length L.

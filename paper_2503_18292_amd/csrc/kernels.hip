@@ -56,19 +56,34 @@ constexpr int kMaxBufferedRecords = 16;
 
 // Copies `count` buffered records (and the chunk spans of the segments that start in them) from
 // LDS to the workspace.  Record r: G * D accumulator floats, then G (max, sum) pairs.
+// A record that covers its whole segment (s_last < 0) is the segment's result but for the
+// division: when the caller's output array is known it goes there directly, normalised exactly as
+// the reduction would (a one-record merge multiplies by 1 and divides by the sum), and the
+// segment's span is left empty, which tells the reduction to skip it.  With many short requests
+// that is nearly every segment, and the reduction launch has next to nothing to do.
 template <int D>
 __device__ __forceinline__ void flush_records(const DecodeParams& p, const float* s_rec, const int* s_slot,
                                               const int* s_seg, const int* s_last, int count, int G,
                                               int rec_stride, int lane) {
   __syncthreads();                                  // the engine's LDS writes (one wavefront per block)
   for (int r = 0; r < count; ++r) {
-    const int64_t slot = s_slot[r];
     const float4* src = reinterpret_cast<const float4*>(s_rec + r * rec_stride);
+    const float2* ml = reinterpret_cast<const float2*>(s_rec + r * rec_stride + G * D);
+    if (s_last[r] < 0) {
+      float4* dst = reinterpret_cast<float4*>(p.out + int64_t(s_seg[r]) * G * D);   // heads kvh*G .. of request b
+      for (int i = lane; i < G * D / 4; i += kWave) {
+        const float l = ml[i / (D / 4)].y;
+        const float inv = l > 0.f ? 1.0f / l : 0.f;
+        const float4 a = src[i];
+        dst[i] = make_float4(a.x * inv, a.y * inv, a.z * inv, a.w * inv);
+      }
+      if (lane == 0) *reinterpret_cast<int2*>(p.ws_meta + int64_t(s_seg[r]) * 2) = make_int2(1, 0);
+      continue;
+    }
+    const int64_t slot = s_slot[r];
     float4* dst = reinterpret_cast<float4*>(p.ws_acc + slot * G * D);
     for (int i = lane; i < G * D / 4; i += kWave) dst[i] = src[i];
-    if (lane < G)
-      reinterpret_cast<float2*>(p.ws_ml + slot * G * 2)[lane] =
-          reinterpret_cast<const float2*>(s_rec + r * rec_stride + G * D)[lane];
+    if (lane < G) reinterpret_cast<float2*>(p.ws_ml + slot * G * 2)[lane] = ml[lane];
     if (lane == 0 && s_seg[r] >= 0)
       *reinterpret_cast<int2*>(p.ws_meta + int64_t(s_seg[r]) * 2) = make_int2(int(blockIdx.x), s_last[r]);
   }
@@ -127,9 +142,10 @@ __global__ __launch_bounds__(kWave) void decode_partial_kernel(const DecodeParam
         }
         rec = s_rec + n_rec * rec_stride;
         if (lane == 0) {
+          const bool whole = p.out != nullptr && tile0 == 0 && n_tiles == units_b - kSegStartUnits;
           s_rslot[n_rec] = slot;
           s_rseg[n_rec] = tile0 == 0 ? seg : -1;
-          s_rlast[n_rec] = last_chunk;
+          s_rlast[n_rec] = whole ? -1 : last_chunk;
         }
         ++n_rec;
       } else if (tile0 == 0 && lane == 0) {
@@ -185,6 +201,7 @@ __global__ __launch_bounds__(kWave * NW) void splitk_reduce_kernel(
   const int64_t seg = int64_t(b) * n_kv_heads + kvh;
   const int2 span = *reinterpret_cast<const int2*>(ws_meta + seg * 2);
   const int c_lo = span.x, c_hi = span.y;
+  if (c_lo > c_hi) return;                // the partial kernel has written this segment's result itself
   float m_star = kNegBig, l_star = 0.f;
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   for (int c0 = c_lo + wave * (R * NG); c0 <= c_hi; c0 += R * NG * NW) {
@@ -395,6 +412,7 @@ __global__ __launch_bounds__(kWave) void splitk_reduce_packed_kernel(
   }
   const int64_t seg = int64_t(b) * n_kv_heads + kvh;
   const int2 span = *reinterpret_cast<const int2*>(ws_meta + seg * 2);
+  if (span.x > span.y) return;            // the partial kernel has written this segment's result itself
   float m_star = kNegBig, l_star = 0.f;
   float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
   for (int c0 = span.x; c0 <= span.y; c0 += 2) {
@@ -664,7 +682,7 @@ int check_partial_args(const jenga_pool* pool, const Geometry& g, int32_t layer,
 int launch_partial(const jenga_pool* pool, int32_t kind, const Geometry& g, int32_t layer, const void* q,
                    int32_t n_q_heads, const void* k_new, const void* v_new, const int32_t* block_table,
                    int32_t bt_stride, const int32_t* seq_lens, int32_t batch, int32_t max_seq_len,
-                   int32_t window, float scale, const Workspace& ws, jenga_stream stream) {
+                   int32_t window, float scale, const Workspace& ws, float* out, jenga_stream stream) {
   if (batch == 0) return JENGA_OK;
   const jenga::Kind& k = *g.kind;
   const int row_bytes = k.desc.head_dim * k.elem_bytes;
@@ -693,6 +711,7 @@ int launch_partial(const jenga_pool* pool, int32_t kind, const Geometry& g, int3
   p.ws_acc = ws.acc;
   p.ws_ml = ws.ml;
   p.ws_meta = ws.meta;
+  p.out = out;
   const int n_part = launch_partitions(g);
   // Every appended row costs its wavefront the latency of a store (loads and stores share one
   // in-order counter): with many short requests -- six or more (request, KV head) segments per
@@ -816,7 +835,7 @@ int jenga_paged_decode_partial(const jenga_pool* pool, int32_t kind, int32_t lay
   rc = split_ws(g, workspace, workspace_bytes, &ws);
   if (rc != JENGA_OK) return rc;
   return launch_partial(pool, kind, g, layer, q, n_q_heads, k_new, v_new, block_table, bt_stride, seq_lens,
-                        batch, max_seq_len, window, scale, ws, stream);
+                        batch, max_seq_len, window, scale, ws, nullptr, stream);
 }
 
 int jenga_splitk_reduce(const jenga_pool* pool, int32_t kind, int32_t n_q_heads,
@@ -842,12 +861,19 @@ int jenga_paged_decode(const jenga_pool* pool, int32_t kind, int32_t layer, cons
                        float* out, jenga_stream stream) {
   if (!out) return JENGA_ERR_INVALID;
   if (!aligned16(out)) return JENGA_ERR_ALIGN;
-  const int rc = jenga_paged_decode_partial(pool, kind, layer, q, n_q_heads, k_new, v_new, block_table, bt_stride,
-                                            seq_lens, batch, max_seq_len, window, scale,
-                                            pages_per_split, workspace, workspace_bytes, stream);
+  Geometry g;
+  int rc = decode_geometry(pool, kind, n_q_heads, batch, max_seq_len, window, pages_per_split, &g);
   if (rc != JENGA_OK) return rc;
-  return jenga_splitk_reduce(pool, kind, n_q_heads, seq_lens, batch, max_seq_len, window,
-                             pages_per_split, workspace, workspace_bytes, out, stream);
+  rc = check_partial_args(pool, g, layer, q, k_new, v_new, block_table, bt_stride, seq_lens, max_seq_len);
+  if (rc != JENGA_OK) return rc;
+  Workspace ws;
+  rc = split_ws(g, workspace, workspace_bytes, &ws);
+  if (rc != JENGA_OK) return rc;
+  // (the partial kernel knows `out`: segments it covers in one piece are finished there)
+  rc = launch_partial(pool, kind, g, layer, q, n_q_heads, k_new, v_new, block_table, bt_stride, seq_lens,
+                      batch, max_seq_len, window, scale, ws, out, stream);
+  if (rc != JENGA_OK) return rc;
+  return launch_reduce(g, n_q_heads, seq_lens, batch, max_seq_len, ws, out, stream);
 }
 
 int jenga_paged_decode_static(const jenga_pool* pool, int32_t kind, int32_t layer, const void* q,
@@ -874,7 +900,7 @@ int jenga_paged_decode_static(const jenga_pool* pool, int32_t kind, int32_t laye
   if (!base) return rc;
   const Workspace ws = carve_ws(g, base);
   rc = launch_partial(pool, kind, g, layer, q, n_q_heads, k_new, v_new, block_table, bt_stride, seq_lens,
-                      batch, max_seq_len, window, scale, ws, stream);
+                      batch, max_seq_len, window, scale, ws, out, stream);
   if (rc != JENGA_OK) return rc;
   return launch_reduce(g, n_q_heads, seq_lens, batch, max_seq_len, ws, out, stream);
 }
