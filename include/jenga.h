@@ -264,7 +264,9 @@ int jenga_decode_num_partitions(const jenga_pool* pool, int32_t kind, int32_t n_
                                 int32_t pages_per_split);
 /* Bytes of split-K workspace jenga_paged_decode needs for these arguments (> 0), or a
  * negative status: one (max, sum, accumulator) record per query head for each of
- * (partitions + batch * n_kv_heads) slots, plus 8 bytes per (request, KV head). */
+ * (partitions + batch * n_kv_heads) slots, plus 8 bytes per (request, KV head), plus 8 bytes per
+ * request for batches above 1024 (whose per-request prefix sums a small kernel of its own leaves
+ * there for the decode kernel; up to 1024 requests every block makes them for itself). */
 int64_t jenga_decode_workspace_bytes(const jenga_pool* pool, int32_t kind, int32_t n_q_heads,
                                      int32_t batch, int32_t max_seq_len, int32_t window,
                                      int32_t pages_per_split);
@@ -297,7 +299,8 @@ int64_t jenga_decode_workspace_bytes(const jenga_pool* pool, int32_t kind, int32
  *   workspace    device, >= jenga_decode_workspace_bytes(...), 16-byte aligned, caller-owned;
  *                holds per-partition (max, sum, accumulator) between the two kernels
  * Runs the partial kernel and the split-K reduction on `stream`.
- * Errors: INVALID, ALIGN, WORKSPACE, UNSUPPORTED (G > 16; batch > 1024), HIP. */
+ * Errors: INVALID, ALIGN, WORKSPACE, UNSUPPORTED (G > 16; batch > 65535; more than 2^30 tiles
+ * over all (request, KV head) pairs), HIP. */
 int jenga_paged_decode(const jenga_pool* pool, int32_t kind, int32_t layer,
                        const void* q, int32_t n_q_heads,
                        const void* k_new, const void* v_new,

@@ -10,7 +10,9 @@
 namespace {
 
 constexpr int kWave = 64;
-constexpr int kMaxBatch = 1024;         // per-request prefix sums are kept in LDS
+constexpr int kMaxBatch = 1024;         // up to here the per-request prefix sums are made by every block, in LDS;
+                                        // larger batches get them from a kernel of their own, through the workspace
+constexpr int kMaxGridBatch = 65535;    // one row of reduction blocks per request: the grid's y limit
 constexpr int kMaxPartitions = 8192;    // bound of the automatic grid (sizes the workspace)
 // Starting on a segment (block-table row, query rows, first loads, final merge and store) costs a
 // wavefront about as long as streaming two tiles (measured: 4.4 to 5 us against 2.5 us per
@@ -45,6 +47,8 @@ struct DecodeParams {
   float* ws_acc;              // [slot][G][D]
   float* ws_ml;               // [slot][G][2]  (running max, running sum)
   int32_t* ws_meta;           // [segment][2]  first and last chunk that hold tiles of the segment
+  const int32_t* ws_incl;     // batch > kMaxBatch: [batch] inclusive prefix sums of the requests' flat units
+  const int32_t* ws_len;      //                    [batch] clamped lengths, negated where the clamp took effect
   float* out;                 // [batch][n_q_heads][D] when the reduction of the same call follows, else NULL:
                               // a record that covers its whole segment is then written there, normalised
 };
@@ -155,6 +159,25 @@ __device__ __forceinline__ int find_request(const int* s_incl, int batch, int x,
   const bool past = i < batch && s_incl[i] > x;
   const unsigned long long hit = __ballot(past);
   return hit ? c0 + __builtin_ctzll(hit) : batch - 1;
+}
+
+// The same search in prefix sums that lie in global memory (batches above kMaxBatch): rounds of
+// 64 probes, each cutting the range to a 64th, then the last 64 entries one per lane.
+__device__ __forceinline__ int find_request_global(const int32_t* incl, int batch, int x, int lane) {
+  int lo = 0, n = batch;
+  while (n > kWave) {
+    const int step = (n + kWave - 1) / kWave;
+    const int first = lane * step;                          // this lane's part: [first, first + step) of the range
+    const bool mine = first < n;
+    const bool past = mine && incl[lo + min(first + step, n) - 1] > x;
+    const unsigned long long hit = __ballot(past);
+    const int f = hit ? __builtin_ctzll(hit) : (n - 1) / step;
+    lo += f * step;
+    n = min(step, n - f * step);
+  }
+  const bool past = lane < n && incl[lo + lane] > x;
+  const unsigned long long hit = __ballot(past);
+  return hit ? lo + __builtin_ctzll(hit) : batch - 1;
 }
 
 // ---- element types ---------------------------------------------------------------

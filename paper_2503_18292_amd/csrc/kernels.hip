@@ -90,17 +90,64 @@ __device__ __forceinline__ void flush_records(const DecodeParams& p, const float
   __syncthreads();                                  // the buffer may be written again
 }
 
+// Batches above kMaxBatch: the prefix sums every decode block needs (see scan_requests) are made
+// once, by one block, and read from the workspace.  Thread t takes the K consecutive requests
+// t*K .. t*K + K - 1.
+__global__ __launch_bounds__(1024) void scan_lengths_kernel(const int32_t* __restrict__ seq_lens, int batch,
+                                                            int max_seq_len, int window, int t_log2,
+                                                            int tile_log2, int n_kv_heads,
+                                                            int32_t* __restrict__ incl, int32_t* __restrict__ lens) {
+  __shared__ int s_wave[16];
+  const int t = threadIdx.x;
+  const int K = (batch + 1023) / 1024;
+  const int first = t * K, last = min(first + K, batch);
+  int total = 0;
+  for (int i = first; i < last; ++i) {
+    const int raw = seq_lens[i];
+    const int Li = min(raw, max_seq_len);
+    lens[i] = raw > max_seq_len ? -Li : Li;
+    total += units_of(Li, window, t_log2, tile_log2) * n_kv_heads;
+  }
+  int scan = total;                                   // inclusive over the wavefront, then over the 16 wavefronts
+#pragma unroll
+  for (int off = 1; off < kWave; off <<= 1) {
+    const int up = __shfl_up(scan, off);
+    if ((t & (kWave - 1)) >= off) scan += up;
+  }
+  if ((t & (kWave - 1)) == kWave - 1) s_wave[t / kWave] = scan;
+  __syncthreads();
+  int before = scan - total;
+  for (int w = 0; w < t / kWave; ++w) before += s_wave[w];
+  for (int i = first; i < last; ++i) {
+    const int Li = abs(lens[i]);
+    before += units_of(Li, window, t_log2, tile_log2) * n_kv_heads;
+    incl[i] = before;
+  }
+}
+
 // One wavefront per partition of the flat tile space (see the head of the file).
-template <class Eng>
+// BIG: the batch exceeds kMaxBatch and the prefix sums come from scan_lengths_kernel.
+template <class Eng, bool BIG>
 __global__ __launch_bounds__(kWave) void decode_partial_kernel(const DecodeParams p) {
-  __shared__ int s_incl[kMaxBatch];
-  __shared__ int s_len[kMaxBatch];
+  __shared__ int s_incl[BIG ? 1 : kMaxBatch];
+  __shared__ int s_len[BIG ? 1 : kMaxBatch];
   __shared__ float s_eng[Eng::kLdsFloats > 0 ? Eng::kLdsFloats : 1];
   __shared__ __align__(16) float s_rec[Eng::kRecFloats];
   __shared__ int s_rslot[kMaxBufferedRecords], s_rseg[kMaxBufferedRecords], s_rlast[kMaxBufferedRecords];
   const int lane = threadIdx.x;
-  const int W = scan_requests(p.seq_lens, p.batch, p.max_seq_len, p.window, p.t_log2, Eng::kTileLog2,
-                              p.n_kv_heads, lane, s_incl, s_len);
+  const int* incl;
+  const int* lens;
+  int W;
+  if constexpr (BIG) {
+    incl = p.ws_incl;
+    lens = p.ws_len;
+    W = incl[p.batch - 1];
+  } else {
+    W = scan_requests(p.seq_lens, p.batch, p.max_seq_len, p.window, p.t_log2, Eng::kTileLog2,
+                      p.n_kv_heads, lane, s_incl, s_len);
+    incl = s_incl;
+    lens = s_len;
+  }
   const int C = chunk_of(p.chunk_tiles, p.min_chunk_tiles, W, gridDim.x);
   const int64_t x0 = int64_t(blockIdx.x) * C;
   if (x0 >= W) return;
@@ -115,12 +162,12 @@ __global__ __launch_bounds__(kWave) void decode_partial_kernel(const DecodeParam
   ids.n_loaded = 0;
   int x = int(x0);
   const int x1 = int(min<int64_t>(W, x0 + C));
-  int b = find_request(s_incl, p.batch, x, lane);
+  int b = BIG ? find_request_global(incl, p.batch, x, lane) : find_request(incl, p.batch, x, lane);
   while (x < x1) {
     // x only grows: the request of the next segment is the same one or a later one
-    while (b < p.batch - 1 && s_incl[b] <= x) ++b;
-    const int start_b = b > 0 ? s_incl[b - 1] : 0;
-    const int units_b = (s_incl[b] - start_b) / p.n_kv_heads;     // start-up units + tiles, per head
+    while (b < p.batch - 1 && incl[b] <= x) ++b;
+    const int start_b = b > 0 ? incl[b - 1] : 0;
+    const int units_b = (incl[b] - start_b) / p.n_kv_heads;       // start-up units + tiles, per head
     const int rem = x - start_b;
     const int kvh = rem / units_b;
     const int seg0 = start_b + kvh * units_b;                     // flat position of the segment
@@ -153,7 +200,7 @@ __global__ __launch_bounds__(kWave) void decode_partial_kernel(const DecodeParam
       }
       // fused append: the chunk that holds the tile of the newest token (position L - 1) writes it
       // (not for a request whose length was clamped to max_seq_len: see scan_requests)
-      const int L_enc = s_len[b];
+      const int L_enc = lens[b];
       const int L = abs(L_enc);
       int append_tile = -1;
       if (p.k_new != nullptr && L_enc > 0) {
@@ -492,23 +539,26 @@ bool aligned16(const void* p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0;
 // Builds: element type x head size x page kind (8-token pages are half blocks) x head count
 // (the powers of two at compile time, 0 = any other count up to 16 at run time).
 template <typename E, int D, bool HALF>
-DecodeFn pick_g(int G) {
+DecodeFn pick_g(int G, bool big) {
+#define JENGA_PICK(GG) (big ? decode_partial_kernel<MatEngine<E, D, GG, HALF>, true> \
+                            : decode_partial_kernel<MatEngine<E, D, GG, HALF>, false>)
   switch (G) {
-    case 1: return decode_partial_kernel<MatEngine<E, D, 1, HALF>>;
-    case 2: return decode_partial_kernel<MatEngine<E, D, 2, HALF>>;
-    case 4: return decode_partial_kernel<MatEngine<E, D, 4, HALF>>;
-    case 8: return decode_partial_kernel<MatEngine<E, D, 8, HALF>>;
-    case 16: return decode_partial_kernel<MatEngine<E, D, 16, HALF>>;
-    default: return decode_partial_kernel<MatEngine<E, D, 0, HALF>>;
+    case 1: return JENGA_PICK(1);
+    case 2: return JENGA_PICK(2);
+    case 4: return JENGA_PICK(4);
+    case 8: return JENGA_PICK(8);
+    case 16: return JENGA_PICK(16);
+    default: return JENGA_PICK(0);
   }
+#undef JENGA_PICK
 }
 
 template <typename E>
-DecodeFn pick_d(int D, bool half_pages, int G) {
+DecodeFn pick_d(int D, bool half_pages, int G, bool big) {
   switch (D) {
-    case 64: return half_pages ? pick_g<E, 64, true>(G) : pick_g<E, 64, false>(G);
-    case 128: return half_pages ? pick_g<E, 128, true>(G) : pick_g<E, 128, false>(G);
-    default: return half_pages ? pick_g<E, 256, true>(G) : pick_g<E, 256, false>(G);
+    case 64: return half_pages ? pick_g<E, 64, true>(G, big) : pick_g<E, 64, false>(G, big);
+    case 128: return half_pages ? pick_g<E, 128, true>(G, big) : pick_g<E, 128, false>(G, big);
+    default: return half_pages ? pick_g<E, 256, true>(G, big) : pick_g<E, 256, false>(G, big);
   }
 }
 
@@ -549,6 +599,9 @@ struct Geometry {
   int n_part_bound;      // partitions the workspace must have room for
   int64_t slots;
   DecodeFn fn;
+  int batch;
+  int tile_log2;         // tokens per tile, as the engine's kTileLog2
+  bool big;              // batch > kMaxBatch: prefix sums through the workspace
 };
 
 // Everything the partial kernel and the reduction must agree on.
@@ -562,7 +615,8 @@ int decode_geometry(const jenga_pool* pool, int32_t kind, int32_t n_q_heads, int
   // a sliding-window kind keeps only the pages of its window resident: a wider view would read
   // pages the allocator has already handed to someone else
   if (k.desc.type == JENGA_WINDOW && (window <= 0 || window > k.desc.window)) return JENGA_ERR_INVALID;
-  if (batch > kMaxBatch) return JENGA_ERR_UNSUPPORTED;
+  // (the reduction's grid has one row of blocks per request)
+  if (batch > kMaxGridBatch) return JENGA_ERR_UNSUPPORTED;
   if (n_q_heads % k.desc.n_kv_heads != 0) return JENGA_ERR_INVALID;
   const int G = n_q_heads / k.desc.n_kv_heads;
   // any number of query heads per KV head up to 16: the engine pads them to the 16 rows of the
@@ -580,8 +634,11 @@ int decode_geometry(const jenga_pool* pool, int32_t kind, int32_t n_q_heads, int
   const int64_t w_max = (max_tiles + kSegStartUnits) * k.desc.n_kv_heads * std::max(batch, 1);
   if (w_max > 0x3fffffff) return JENGA_ERR_UNSUPPORTED;
   const bool half_pages = k.t_log2 == 3;
-  out->fn = k.desc.dtype == JENGA_F32 ? pick_d<F32>(k.desc.head_dim, half_pages, G)
-                                      : pick_d<BF16>(k.desc.head_dim, half_pages, G);
+  out->batch = batch;
+  out->tile_log2 = tile_tokens == 16 ? 4 : 6;
+  out->big = batch > kMaxBatch;
+  out->fn = k.desc.dtype == JENGA_F32 ? pick_d<F32>(k.desc.head_dim, half_pages, G, out->big)
+                                      : pick_d<BF16>(k.desc.head_dim, half_pages, G, out->big);
   if (out->fn == nullptr) return JENGA_ERR_UNSUPPORTED;
   const int64_t tile_bytes = int64_t(tile_tokens) * row * 2;
   out->min_chunk_tiles = int(std::max<int64_t>(1, (64 * 1024) / tile_bytes));
@@ -603,11 +660,12 @@ int launch_partitions(const Geometry& g) {
 }
 
 // Workspace layout: accumulators [slot][G][D], (max, sum) pairs [slot][G][2], then the
-// (first chunk, last chunk) pair of every (request, KV head) segment.
+// (first chunk, last chunk) pair of every (request, KV head) segment, then, for batches above
+// kMaxBatch, the requests' prefix sums and clamped lengths.
 int64_t segments_of(const Geometry& g) { return g.slots - g.n_part_bound; }
 
 int64_t workspace_bytes_for(const Geometry& g) {
-  return g.slots * g.G * (g.kind->desc.head_dim + 2) * 4 + segments_of(g) * 8;
+  return g.slots * g.G * (g.kind->desc.head_dim + 2) * 4 + segments_of(g) * 8 + (g.big ? int64_t(g.batch) * 8 : 0);
 }
 
 int hip_status() { return hipGetLastError() == hipSuccess ? JENGA_OK : JENGA_ERR_HIP; }
@@ -616,6 +674,8 @@ struct Workspace {
   float* acc;
   float* ml;
   int32_t* meta;
+  int32_t* incl;    // big batches only
+  int32_t* len;
 };
 
 // Carves the three arrays out of `base` (the layout only depends on the geometry).
@@ -624,6 +684,8 @@ Workspace carve_ws(const Geometry& g, void* base) {
   ws.acc = static_cast<float*>(base);
   ws.ml = ws.acc + g.slots * g.G * g.kind->desc.head_dim;
   ws.meta = reinterpret_cast<int32_t*>(ws.ml + g.slots * g.G * 2);
+  ws.incl = ws.meta + segments_of(g) * 2;
+  ws.len = ws.incl + g.batch;
   return ws;
 }
 
@@ -712,6 +774,8 @@ int launch_partial(const jenga_pool* pool, int32_t kind, const Geometry& g, int3
   p.ws_ml = ws.ml;
   p.ws_meta = ws.meta;
   p.out = out;
+  p.ws_incl = ws.incl;
+  p.ws_len = ws.len;
   const int n_part = launch_partitions(g);
   // Every appended row costs its wavefront the latency of a store (loads and stores share one
   // in-order counter): with many short requests -- six or more (request, KV head) segments per
@@ -724,6 +788,9 @@ int launch_partial(const jenga_pool* pool, int32_t kind, const Geometry& g, int3
     p.k_new = nullptr;
     p.v_new = nullptr;
   }
+  if (g.big)
+    hipLaunchKernelGGL(scan_lengths_kernel, dim3(1), dim3(1024), 0, static_cast<hipStream_t>(stream), seq_lens,
+                       batch, max_seq_len, window, k.t_log2, g.tile_log2, k.desc.n_kv_heads, ws.incl, ws.len);
   hipLaunchKernelGGL(g.fn, dim3(unsigned(n_part)), dim3(kWave), 0, static_cast<hipStream_t>(stream), p);
   return hip_status();
 }

@@ -1,6 +1,6 @@
-"""GPU parity at the limits of what the kernels accept: the largest batch, a batch that needs
-several rounds of the per-block length scan, one very long request next to very short ones,
-and lengths above the stated maximum (clamped by the kernels)."""
+"""GPU parity at the limits of what the kernels accept: the largest batch whose prefix sums every
+block makes for itself, batches beyond it (prefix sums from a kernel of their own), one very long
+request next to very short ones, and lengths above the stated maximum (clamped by the kernels)."""
 import numpy as np
 import pytest
 import torch
@@ -11,7 +11,7 @@ from test_gpu_parity import _runner, check_against_oracle, check_append_landed, 
 
 pytestmark = pytest.mark.gpu
 
-MAX_BATCH = 1024      # stated in the header of the decode entry points
+MAX_BATCH = 1024      # the largest batch whose prefix sums are made per block, in LDS
 
 
 @pytest.mark.parametrize("batch,T,dtype,D,G,window", [
@@ -48,21 +48,32 @@ def test_many_segments_per_wavefront_append_runs_in_front(dtype, window):
     r.close()
 
 
-def test_batch_above_the_limit_is_refused():
+@pytest.mark.parametrize("batch,T,dtype,D,G,window,hi", [
+    (MAX_BATCH + 1, 16, "bf16", 128, 4, 0, 60),      # one request past the per-block scan
+    (4096, 16, "bf16", 128, 4, 0, 90),               # the case the larger decode batches of the paper point to
+    (3000, 32, "f32", 64, 2, 50, 120),               # fp32 K/V, sliding window, 32-token pages
+    (5000, 8, "bf16", 64, 3, 0, 40),                 # 8-token pages, run-time head count, three rounds of the search
+])
+def test_batches_beyond_the_per_block_scan(batch, T, dtype, D, G, window, hi):
+    print(f"[case] big batch={batch} T={T} {dtype} D={D} G={G} W={window}", flush=True)
+    typ = WINDOW if window else FULL
+    cfg = custom_cfg(dtype, D, 2 * G, 2, typ, window=window, batch=batch, lo=0, hi=hi, n_layers=1, T=T)
+    r = _runner(cfg, 7 + batch)
+    prepare(r)
+    r.device_step()
+    check_against_oracle(r, cfg.name)
+    check_append_landed(r)
+    r.close()
+
+
+def test_batch_above_the_grid_limit_is_refused():
     import paper_2503_18292_amd as J
     cfg = custom_cfg("bf16", 128, 4, 2, FULL, batch=2, n_layers=1)
     r = _runner(cfg, 1)
-    prepare(r)
-    B = MAX_BATCH + 1
-    q = torch.zeros(B, 4, 128, dtype=torch.bfloat16, device="cuda")
-    table = torch.zeros(B, r.tables[0].shape[1], dtype=torch.int32, device="cuda")
-    lens = torch.ones(B, dtype=torch.int32, device="cuda")
-    out = torch.empty(B, 4, 128, dtype=torch.float32, device="cuda")
-    ws = torch.empty(1 << 22, dtype=torch.float32, device="cuda")
     with pytest.raises(J.JengaError) as e:
-        r.pool.paged_decode(0, 0, q, table, lens, r.max_len[0], 0, 0.1, ws, out)
+        r.pool.decode_workspace_bytes(0, 4, 65536, 64)
     assert e.value.status == -6      # JENGA_ERR_UNSUPPORTED
-    torch.cuda.synchronize()
+    assert r.pool.decode_workspace_bytes(0, 4, 65535, 64) > 0
     r.close()
 
 

@@ -242,8 +242,10 @@ def test_partition_geometry_and_workspace_queries():
         tiny_lib.decode_workspace_bytes(0, 34, 4, 256)    # G = 17
     assert e.value.status == -6
     with pytest.raises(J.JengaError) as e:
-        lib.decode_workspace_bytes(0, 16, 5000, 8193)    # batch beyond the kernels' limit
+        lib.decode_workspace_bytes(0, 16, 70000, 8193)   # batch beyond the kernels' limit
     assert e.value.status == -6
+    # batches above 1024 carry their prefix sums in the workspace: 8 bytes per request more
+    assert lib.decode_workspace_bytes(0, 16, 5000, 8193) == (n + 5000 * 8) * 2 * (256 + 2) * 4 + 5000 * 8 * 8 + 5000 * 8
     with pytest.raises(J.JengaError):
         lib.decode_workspace_bytes(0, 16, 64, 8193, pages_per_split=-1)
     # a sliding-window kind cannot be read with a wider window than it keeps resident
