@@ -74,7 +74,8 @@ typedef struct {
   int32_t n_layers;         /* >= 1 */
   int32_t n_kv_heads;       /* attention kinds: >= 1 */
   int32_t head_dim;         /* attention kinds: 64, 128 or 256 */
-  int32_t tokens_per_page;  /* attention kinds: power of two in [8, 128]; OPAQUE: 1 */
+  int32_t tokens_per_page;  /* attention kinds: 1 .. 4096 (Sec. 4.1 footnote: arbitrary; 16, 32, 64, 128 and 8
+                               run on the fast addressing paths); OPAQUE: 1 */
   int32_t window;           /* WINDOW kinds: > 0; others: 0 */
   int32_t reserved;         /* 0 */
   int64_t small_page_bytes; /* 0: n_layers * slice for attention kinds; otherwise at least that,

@@ -27,7 +27,8 @@ struct DecodeParams {
   int64_t small_bytes;        // page stride
   int32_t head_stride;        // bytes between KV heads inside a layer slice: 2 * T * D * e
   int32_t v_offset;           // bytes from a head's K rows to its V rows: T * D * e
-  int32_t t_log2;
+  int32_t t_log2;             // log2 of the tokens per page, or minus the tokens per page if that is no power of two
+  int32_t tokens_per_page;
   int32_t n_kv_heads;
   int32_t n_q_heads;
   int32_t group;           // query heads per KV head
@@ -53,13 +54,18 @@ struct DecodeParams {
                               // a record that covers its whole segment is then written there, normalised
 };
 
+// Page of a token and first token of a page; t_log2 as in DecodeParams (negative: minus the page
+// size, which is then no power of two and costs a division).
+__device__ __forceinline__ int page_of_token(int t_log2, int t) { return t_log2 >= 0 ? t >> t_log2 : t / -t_log2; }
+__device__ __forceinline__ int first_token_of(int t_log2, int page) { return t_log2 >= 0 ? page << t_log2 : page * -t_log2; }
+
 // Visible pages [p_lo, p_hi) and first visible token of a request of length L.
 __device__ __forceinline__ void visible_pages(int L, int window, int t_log2, int* lo_tok,
                                               int* p_lo, int* p_hi) {
   const int lo = window > 0 ? max(0, L - window) : 0;
   *lo_tok = lo;
-  *p_lo = lo >> t_log2;
-  *p_hi = (L + (1 << t_log2) - 1) >> t_log2;
+  *p_lo = page_of_token(t_log2, lo);
+  *p_hi = page_of_token(t_log2, L - 1) + 1;                 // L >= 1
 }
 
 // Units of the flat space one (request, KV head) segment takes: kSegStartUnits, then one per
@@ -68,7 +74,7 @@ __device__ __forceinline__ int units_of(int L, int window, int t_log2, int tile_
   if (L <= 0) return 0;
   int lo_tok, p_lo, p_hi;
   visible_pages(L, window, t_log2, &lo_tok, &p_lo, &p_hi);
-  return kSegStartUnits + ((((p_hi - p_lo) << t_log2) + (1 << tile_log2) - 1) >> tile_log2);
+  return kSegStartUnits + ((first_token_of(t_log2, p_hi - p_lo) + (1 << tile_log2) - 1) >> tile_log2);
 }
 
 // Inclusive prefix sums of units * n_kv_heads per request into LDS, lengths next to them: the
@@ -202,6 +208,7 @@ struct PageIds {
   int lane;
   int max_id;
   int reg0, reg1;       // two scalars, not an array: an indexed member would live in scratch memory
+  int next_run;         // k_stream_in: first page of the run whose entry triggers the next load
 
   // A table entry that is negative or past the pool (a caller error: pages of the visible
   // range must be resident) is clamped, so the kernel reads wrong data rather than faulting.
@@ -216,16 +223,36 @@ struct PageIds {
   __device__ __forceinline__ void init(const int32_t* r, int n, int l, int max_page_id) {
     if (r == row && n <= n_loaded) {
       n_pages = n;
+      next_run = kWave;
       return;
     }
     row = r; n_pages = n; lane = l; max_id = max_page_id;
     n_loaded = n;
+    next_run = kWave;
     reg0 = fetch(0);
     reg1 = fetch(kWave);
   }
   __device__ __forceinline__ int get(int page_rel) const {
     const int r = (page_rel & kWave) ? reg1 : reg0;
     return __builtin_amdgcn_readlane(r, page_rel & (kWave - 1));
+  }
+  // The id of a page that differs from lane to lane (pages of any size: a 16-token block then
+  // takes its rows from several pages): two cross-lane reads, one per register.
+  __device__ __forceinline__ int get_lane(int page_rel) const {
+    const int a = __shfl(reg0, page_rel & (kWave - 1));
+    const int b = __shfl(reg1, page_rel & (kWave - 1));
+    return (page_rel & kWave) ? b : a;
+  }
+  // The same for pages of any size, where a run of 64 pages need not begin with a tile: called with
+  // the page of the tile's first token, it loads run c+1 once the stream is in run c.
+  __device__ __forceinline__ void k_stream_in(int page_rel) {
+    if (page_rel >= next_run && next_run + kWave < n_pages) {
+      const int next = fetch(next_run + kWave);
+      if (next_run & kWave) reg0 = next;
+      else reg1 = next;
+      next_run += kWave;
+      n_loaded = 0;
+    }
   }
   // Call after the K stream has issued the loads of a tile starting at page_rel.
   __device__ __forceinline__ void k_stream_at(int page_rel) {

@@ -33,15 +33,21 @@ namespace {
 // (its rounding and the rounding of the remainder, 16 significant bits together) in two
 // products, so the result stays within fp32 rounding of an fp32 weighted sum -- the matrix
 // cores are idle most of the time anyway.
-// HALF_: the pages hold 8 tokens, half a block (a build of its own, so that the usual case keeps
+// MODE_ 0: pages of 16, 32, 64 or 128 tokens, i.e. 1, 2, 4 or 8 whole blocks.
+// MODE_ 1: the pages hold 8 tokens, half a block (a build of its own, so that the usual case keeps
 // a scalar page address plus a constant lane offset for every load).
+// MODE_ 2: pages of any other size (1, 2, 4, 24 ... tokens): the rows of a block come from
+// whatever pages its 16 tokens fall into, every lane looks up the page of the row it loads
+// (a division and two cross-lane reads per load address).  The paper leaves the number of
+// tokens per page open (Sec. 4.1 footnote); this build serves it, without the scalar addressing
+// that makes the other two fast.
 // fp32 K/V takes the same road with v_mfma_f32_16x16x4_f32 (A row n / B column n, k = j; result as
 // above): lane (n, j) holds the four floats d = 16c + 4j + e of token n from each 16-byte load, and
 // since the order inside the contraction is free, product (c, e) pairs them with the same four
 // floats of the query rows.  For the values, product s of a block contracts over tokens 4j + s:
 // the probability is register s of the lane's score result, and V[4j + s][16 blk + n] is one float
 // per lane, read from the row-major LDS copy with an ordinary 4-byte read.
-template <typename E_, int D_, int G_, bool HALF_>
+template <typename E_, int D_, int G_, int MODE_>
 struct MatEngine {
   using E = E_;
   static constexpr bool F32K = E::kBytes == 4;
@@ -103,19 +109,23 @@ struct MatEngine {
     // 4 or 8 blocks: block q (counted from the first visible page) lies in page q >> sh at row
     // (q & sub_mask) * 16.  An 8-token page is half a block: a block takes its rows 0..7 from one
     // page and its rows 8..15 from the next.
-    constexpr bool t8 = HALF_;
+    constexpr bool t8 = MODE_ == 1;
+    constexpr bool gen = MODE_ == 2;
     const int G = G_ ? G_ : p.group;                           // query heads per KV head, at most 16
-    const int sh = t8 ? 0 : p.t_log2 - 4;
+    const int sh = (t8 || gen) ? 0 : p.t_log2 - 4;
     const int sub_mask = (1 << sh) - 1;
+    const int Tp = p.tokens_per_page;                          // (used by the any-size mode only)
     int lo_tok, p_lo, p_hi;
     visible_pages(L, p.window, p.t_log2, &lo_tok, &p_lo, &p_hi);
     const int blk0 = tile0 * PPT;                              // first block of the chunk
-    const int tot_blk = t8 ? (p_hi - p_lo + 1) >> 1 : (p_hi - p_lo) << sh;
+    const int tot_blk = gen ? ((p_hi - p_lo) * Tp + T - 1) / T : t8 ? (p_hi - p_lo + 1) >> 1 : (p_hi - p_lo) << sh;
     const int n_blk = min(n_tiles * PPT, tot_blk - blk0);
-    const int page0 = p_lo + (t8 ? 2 * blk0 : blk0 >> sh);
-    const int off0 = t8 ? 0 : blk0 & sub_mask;                 // place of the first block inside page0
-    const int n_pages = t8 ? min(2 * n_blk, p_hi - page0) : (off0 + n_blk + sub_mask) >> sh;
-    const int tok0 = (p_lo << p.t_log2) + blk0 * T;
+    const int page0 = p_lo + (gen ? blk0 * T / Tp : t8 ? 2 * blk0 : blk0 >> sh);
+    const int off0 = (t8 || gen) ? 0 : blk0 & sub_mask;        // place of the first block inside page0
+    const int off_tok = gen ? blk0 * T - (page0 - p_lo) * Tp : 0;   // any size: token of page0 the chunk starts at
+    const int n_pages = gen ? min((off_tok + n_blk * T + Tp - 1) / Tp, p_hi - page0)
+                        : t8 ? min(2 * n_blk, p_hi - page0) : (off0 + n_blk + sub_mask) >> sh;
+    const int tok0 = first_token_of(p.t_log2, p_lo) + blk0 * T;
     char* v_lds = reinterpret_cast<char*>(lds);
 
     ids.init(p.block_table + int64_t(b) * p.bt_stride + page0, n_pages, lane, p.max_page_id);
@@ -124,7 +134,7 @@ struct MatEngine {
     const int v_row = lane / LPT;                                        // V loads: row v_row + TPL * c of the page
     const char* kv_base = p.layer_base + int64_t(kvh) * p.head_stride;   // wave-uniform
     const unsigned k_loff = (t8 ? n & 7 : n) * ROW + j * 16;             // A operand of the score product: row n of the block
-    const unsigned v_loff = p.v_offset + v_row * ROW + (lane % LPT) * 16;
+    const unsigned v_loff = p.v_offset + (gen ? 0 : v_row * ROW) + (lane % LPT) * 16;
     const unsigned lds_wr = v_row * LROW + (lane % LPT) * 16;            // this lane's V bytes (+ row offset)
     const unsigned lds_rd = (4 * j + (n >> 2)) * LROW + (n & 3) * 8;     // transposed read (+ page, + block)
 
@@ -151,12 +161,22 @@ struct MatEngine {
       const int q = off0 + r;
       return kv_base + int64_t(ids.get(q >> sh)) * p.small_bytes + ((q & sub_mask) * T + 8 * h) * ROW;
     };
+    // Pages of any size: address of the row of chunk-relative token t (a different one in every
+    // lane) in this KV head's K rows.  Tokens past the last page (the tail of the last block, masked
+    // like any token >= L) read the last page.
+    auto row_of_token = [&](int t) -> const char* {
+      const int tt = off_tok + t;
+      const int pg = tt / Tp;
+      return kv_base + int64_t(ids.get_lane(min(pg, n_pages - 1))) * p.small_bytes + (tt - pg * Tp) * ROW;
+    };
     auto load_k = [&](int tile, u32x4* buf) {
 #pragma unroll
       for (int pp = 0; pp < PPT; ++pp) {
         const int r = tile * PPT + pp;
         if (PPT == 1 || r < n_blk) {
-          const char* src = half_base(r, 0) + k_loff;                    // wave-uniform base + lane offset
+          const char* src;
+          if constexpr (gen) src = row_of_token(r * T + n) + j * 16;
+          else src = half_base(r, 0) + k_loff;                           // wave-uniform base + lane offset
           if constexpr (t8) {
             const char* hi = half_base(r, 1);                            // taken by all lanes: it reads a lane
             if (n & 8) src = hi + k_loff;
@@ -175,12 +195,19 @@ struct MatEngine {
       for (int pp = 0; pp < PPT; ++pp) {
         const int r = tile * PPT + pp;
         if (PPT == 1 || r < n_blk) {
-          const char* lo = half_base(r, 0);
-          const char* hi = t8 ? half_base(r, 1) : lo + 8 * ROW;
+          if constexpr (gen) {
 #pragma unroll
-          for (int c = 0; c < KCH; ++c) {                    // load c covers rows TPL * c .. TPL * c + TPL - 1
-            const char* src = (((TPL * c) & 8) ? hi : lo) + ((TPL * c) & 7) * ROW;     // wave-uniform
-            buf[pp * KCH + c] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + v_loff));
+            for (int c = 0; c < KCH; ++c)                    // load c covers rows TPL * c .. TPL * c + TPL - 1
+              buf[pp * KCH + c] = __builtin_nontemporal_load(
+                  reinterpret_cast<const u32x4*>(row_of_token(r * T + TPL * c + v_row) + v_loff));
+          } else {
+            const char* lo = half_base(r, 0);
+            const char* hi = t8 ? half_base(r, 1) : lo + 8 * ROW;
+#pragma unroll
+            for (int c = 0; c < KCH; ++c) {                  // load c covers rows TPL * c .. TPL * c + TPL - 1
+              const char* src = (((TPL * c) & 8) ? hi : lo) + ((TPL * c) & 7) * ROW;     // wave-uniform
+              buf[pp * KCH + c] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(src + v_loff));
+            }
           }
         } else {
 #pragma unroll
@@ -190,7 +217,9 @@ struct MatEngine {
     };
     // the K stream tells the page-id registers when it enters a new page
     auto k_entered = [&](int tile) {
-      if (t8) {
+      if (gen) {
+        ids.k_stream_in((off_tok + tile * PPT * T) / Tp);
+      } else if (t8) {
         ids.k_stream_at(2 * tile * PPT);
       } else {
         const int q = off0 + tile * PPT;
@@ -212,10 +241,10 @@ struct MatEngine {
     // tile that takes them in (often the last of the segment) does not wait for them.
     u32x4 k_app[KCH], v_app = u32x4{0, 0, 0, 0};
     int raw_new = -1;
-    const int rel = (L - 1) - (p_lo << p.t_log2);                // the new token, counted from the first visible page
+    const int rel = (L - 1) - first_token_of(p.t_log2, p_lo);    // the new token, counted from the first visible page
     const int r_new = (rel >> 4) - blk0;                         // its block, relative to the chunk
     const int row_new = rel & 15;                                // its row in the block
-    const int page_new = t8 ? 2 * r_new + (row_new >> 3) : (off0 + r_new) >> sh;
+    const int page_new = gen ? (off_tok + r_new * T + row_new) / Tp : t8 ? 2 * r_new + (row_new >> 3) : (off0 + r_new) >> sh;
 #pragma unroll
     for (int c = 0; c < KCH; ++c) k_app[c] = u32x4{0, 0, 0, 0};
     if (append_tile >= 0) {
@@ -374,7 +403,12 @@ struct MatEngine {
     // (The tile of the new token is the last of its segment, so the page-id registers still hold
     // its page.)
     if (append_tile >= 0 && raw_new >= 0 && raw_new <= p.max_page_id) {
-      char* dst = const_cast<char*>(half_base(r_new, row_new >> 3)) + (row_new & 7) * ROW;
+      char* dst;
+      if constexpr (gen)
+        dst = const_cast<char*>(kv_base) + int64_t(ids.get(page_new)) * p.small_bytes +
+              (off_tok + r_new * T + row_new - page_new * Tp) * ROW;
+      else
+        dst = const_cast<char*>(half_base(r_new, row_new >> 3)) + (row_new & 7) * ROW;
       if (n == row_new) {
 #pragma unroll
         for (int c = 0; c < KCH; ++c) *reinterpret_cast<u32x4*>(dst + j * 16 + c * 64) = k_app[c];

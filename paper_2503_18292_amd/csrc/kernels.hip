@@ -206,7 +206,7 @@ __global__ __launch_bounds__(kWave) void decode_partial_kernel(const DecodeParam
       if (p.k_new != nullptr && L_enc > 0) {
         int lo_tok, p_lo, p_hi;
         visible_pages(L, p.window, p.t_log2, &lo_tok, &p_lo, &p_hi);
-        const int t_pos = ((L - 1) - (p_lo << p.t_log2)) >> Eng::kTileLog2;
+        const int t_pos = ((L - 1) - first_token_of(p.t_log2, p_lo)) >> Eng::kTileLog2;
         if (t_pos >= tile0 && t_pos < tile0 + n_tiles) append_tile = t_pos - tile0;
       }
       Eng::run(p, lane, b, kvh, L, tile0, n_tiles, append_tile, slot, rec, ids, s_eng);
@@ -338,13 +338,13 @@ __global__ __launch_bounds__(256) void kv_append_kernel(
   const int L = seq_lens[b];
   if (L <= 0 || L > max_len) return;
   const int pos = L - 1;
-  const int page = pos >> t_log2;
+  const int page = page_of_token(t_log2, pos);
   if (page >= bt_stride) return;
   const int sid = block_table[int64_t(b) * bt_stride + page];
   if (sid < 0 || sid > max_page_id) return;
   const char* src = (is_v ? v_new : k_new) + (int64_t(b) * n_kv_heads + h) * row_bytes + c * 16;
   char* dst = layer_base + int64_t(sid) * small_bytes + int64_t(h) * head_stride +
-              (is_v ? v_offset : 0) + (pos & ((1 << t_log2) - 1)) * row_bytes + c * 16;
+              (is_v ? v_offset : 0) + (pos - first_token_of(t_log2, page)) * row_bytes + c * 16;
   *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
 }
 
@@ -369,12 +369,13 @@ __global__ __launch_bounds__(256) void kv_write_range_kernel(
   const int b = lo;
   if (tok >= cu_tokens[b + 1]) return;            // padding rows past the last request
   const int pos = start_pos[b] + (tok - cu_tokens[b]);
-  const int page = pos >> t_log2;
-  if (pos < 0 || page >= bt_stride) return;
+  if (pos < 0) return;
+  const int page = page_of_token(t_log2, pos);
+  if (page >= bt_stride) return;
   const int sid = block_table[int64_t(b) * bt_stride + page];
   if (sid < 0 || sid > max_page_id) return;       // page not resident (e.g. already slid out)
   const int chunks = row_bytes / 16;              // 16-byte pieces per (head, K or V) row
-  char* page_base = layer_base + int64_t(sid) * small_bytes + (pos & ((1 << t_log2) - 1)) * row_bytes;
+  char* page_base = layer_base + int64_t(sid) * small_bytes + (pos - first_token_of(t_log2, page)) * row_bytes;
   const char* k_row = k_src + int64_t(tok) * n_kv_heads * row_bytes;
   const char* v_row = v_src + int64_t(tok) * n_kv_heads * row_bytes;
   for (int i = threadIdx.x; i < 2 * n_kv_heads * chunks; i += blockDim.x) {
@@ -538,28 +539,37 @@ bool aligned16(const void* p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0;
 
 // Builds: element type x head size x page kind (8-token pages are half blocks) x head count
 // (the powers of two at compile time, 0 = any other count up to 16 at run time).
-template <typename E, int D, bool HALF>
+// Builds: element type x head size x page mode (whole blocks, half blocks; any other page size
+// in a build that takes the head count at run time) x head count (the powers of two at compile
+// time, 0 = any other count up to 16 at run time) x batch range.
+template <typename E, int D, int MODE>
 DecodeFn pick_g(int G, bool big) {
-#define JENGA_PICK(GG) (big ? decode_partial_kernel<MatEngine<E, D, GG, HALF>, true> \
-                            : decode_partial_kernel<MatEngine<E, D, GG, HALF>, false>)
-  switch (G) {
-    case 1: return JENGA_PICK(1);
-    case 2: return JENGA_PICK(2);
-    case 4: return JENGA_PICK(4);
-    case 8: return JENGA_PICK(8);
-    case 16: return JENGA_PICK(16);
-    default: return JENGA_PICK(0);
+#define JENGA_PICK(GG) (big ? decode_partial_kernel<MatEngine<E, D, GG, MODE>, true> \
+                            : decode_partial_kernel<MatEngine<E, D, GG, MODE>, false>)
+  if constexpr (MODE == 2) {
+    return JENGA_PICK(0);
+  } else {
+    switch (G) {
+      case 1: return JENGA_PICK(1);
+      case 2: return JENGA_PICK(2);
+      case 4: return JENGA_PICK(4);
+      case 8: return JENGA_PICK(8);
+      case 16: return JENGA_PICK(16);
+      default: return JENGA_PICK(0);
+    }
   }
 #undef JENGA_PICK
 }
 
 template <typename E>
-DecodeFn pick_d(int D, bool half_pages, int G, bool big) {
+DecodeFn pick_d(int D, int mode, int G, bool big) {
+#define JENGA_PICK_MODE(DD) (mode == 0 ? pick_g<E, DD, 0>(G, big) : mode == 1 ? pick_g<E, DD, 1>(G, big) : pick_g<E, DD, 2>(G, big))
   switch (D) {
-    case 64: return half_pages ? pick_g<E, 64, true>(G, big) : pick_g<E, 64, false>(G, big);
-    case 128: return half_pages ? pick_g<E, 128, true>(G, big) : pick_g<E, 128, false>(G, big);
-    default: return half_pages ? pick_g<E, 256, true>(G, big) : pick_g<E, 256, false>(G, big);
+    case 64: return JENGA_PICK_MODE(64);
+    case 128: return JENGA_PICK_MODE(128);
+    default: return JENGA_PICK_MODE(256);
   }
+#undef JENGA_PICK_MODE
 }
 
 // Partitions of the automatic mode: resident blocks of `fn`, at most one per SIMD, a multiple
@@ -633,12 +643,13 @@ int decode_geometry(const jenga_pool* pool, int32_t kind, int32_t n_q_heads, int
   const int64_t max_tiles = (max_pages * T + tile_tokens - 1) / tile_tokens;
   const int64_t w_max = (max_tiles + kSegStartUnits) * k.desc.n_kv_heads * std::max(batch, 1);
   if (w_max > 0x3fffffff) return JENGA_ERR_UNSUPPORTED;
-  const bool half_pages = k.t_log2 == 3;
+  // whole 16-token blocks per page, half blocks, or any other page size
+  const int mode = (T >= 16 && (T & (T - 1)) == 0) ? 0 : T == 8 ? 1 : 2;
   out->batch = batch;
   out->tile_log2 = tile_tokens == 16 ? 4 : 6;
   out->big = batch > kMaxBatch;
-  out->fn = k.desc.dtype == JENGA_F32 ? pick_d<F32>(k.desc.head_dim, half_pages, G, out->big)
-                                      : pick_d<BF16>(k.desc.head_dim, half_pages, G, out->big);
+  out->fn = k.desc.dtype == JENGA_F32 ? pick_d<F32>(k.desc.head_dim, mode, G, out->big)
+                                      : pick_d<BF16>(k.desc.head_dim, mode, G, out->big);
   if (out->fn == nullptr) return JENGA_ERR_UNSUPPORTED;
   const int64_t tile_bytes = int64_t(tile_tokens) * row * 2;
   out->min_chunk_tiles = int(std::max<int64_t>(1, (64 * 1024) / tile_bytes));
@@ -754,6 +765,7 @@ int launch_partial(const jenga_pool* pool, int32_t kind, const Geometry& g, int3
   p.head_stride = 2 * k.desc.tokens_per_page * row_bytes;
   p.v_offset = k.desc.tokens_per_page * row_bytes;
   p.t_log2 = k.t_log2;
+  p.tokens_per_page = k.desc.tokens_per_page;
   p.n_kv_heads = k.desc.n_kv_heads;
   p.n_q_heads = n_q_heads;
   p.group = g.G;

@@ -31,16 +31,22 @@ int derive_kind(const jenga_kind_desc& d, Kind* k) {
   k->elem_bytes = d.dtype == JENGA_F32 ? 4 : 2;
   if (is_attention(d.type)) {
     if (d.n_kv_heads < 1 || d.head_dim < 1) return JENGA_ERR_INVALID;
-    if (!is_pow2(d.tokens_per_page) || d.tokens_per_page < 8 || d.tokens_per_page > 128)
-      return JENGA_ERR_UNSUPPORTED;
+    // any page size (Sec. 4.1 footnote: the number of tokens per page is arbitrary) whose K rows
+    // and V rows stay 16-byte aligned
+    if (d.tokens_per_page < 1 || d.tokens_per_page > 4096) return JENGA_ERR_UNSUPPORTED;
     if (d.head_dim != 64 && d.head_dim != 128 && d.head_dim != 256) return JENGA_ERR_UNSUPPORTED;
     if (d.type == JENGA_WINDOW ? d.window <= 0 : d.window != 0) return JENGA_ERR_INVALID;
     k->slice_bytes = int64_t(2) * d.n_kv_heads * d.tokens_per_page * d.head_dim * k->elem_bytes;
     const int64_t need = k->slice_bytes * d.n_layers;
     k->small_bytes = d.small_page_bytes == 0 ? need : d.small_page_bytes;
     if (k->small_bytes < need) return JENGA_ERR_INVALID;
-    k->t_log2 = 0;
-    while ((1 << k->t_log2) < d.tokens_per_page) ++k->t_log2;
+    if (is_pow2(d.tokens_per_page)) {
+      k->t_log2 = 0;
+      while ((1 << k->t_log2) < d.tokens_per_page) ++k->t_log2;
+    } else {
+      k->t_log2 = -d.tokens_per_page;        // the kernels divide
+    }
+    if ((int64_t(d.tokens_per_page) * d.head_dim * k->elem_bytes) % 16 != 0) return JENGA_ERR_ALIGN;
   } else {
     // an OPAQUE page is one unit: request lengths of such a kind count pages
     if (d.small_page_bytes <= 0 || d.window != 0 || d.tokens_per_page != 1) return JENGA_ERR_INVALID;

@@ -18,7 +18,7 @@ struct Kind {
   int64_t slice_bytes = 0;   // one layer's K+V for one page of tokens (0 for OPAQUE)
   int64_t per_large = 0;     // r_k
   int32_t elem_bytes = 0;
-  int32_t t_log2 = 0;
+  int32_t t_log2 = 0;        // log2(tokens_per_page), or -tokens_per_page when that is no power of two
 
   // level 2 state.  A small page is used (bit in `used`: it has references), evictable
   // (bit in `cached`: valid contents, no references; Sec. 5.4) or empty (neither).

@@ -42,7 +42,8 @@ def write_contexts_through_library(r, n_chunks=2, pad_rows=3):
 @pytest.mark.parametrize("dtype,D,G,typ,window,T", [
     ("bf16", 256, 2, FULL, 0, 16), ("bf16", 128, 4, WINDOW, 100, 16), ("f32", 64, 2, FULL, 0, 16),
     ("bf16", 128, 4, CROSS, 0, 16), ("f32", 128, 1, WINDOW, 33, 16), ("bf16", 128, 8, FULL, 0, 64),
-    ("bf16", 64, 16, WINDOW, 150, 32), ("f32", 256, 2, FULL, 0, 8)])
+    ("bf16", 64, 16, WINDOW, 150, 32), ("f32", 256, 2, FULL, 0, 8), ("bf16", 128, 4, FULL, 0, 1),
+    ("bf16", 128, 2, WINDOW, 70, 24), ("f32", 64, 4, CROSS, 0, 5)])
 def test_write_range_then_decode(dtype, D, G, typ, window, T):
     print(f"[case] write_range {dtype} D={D} G={G} {typ} W={window} T={T}", flush=True)
     cfg = custom_cfg(dtype, D, 2 * G, 2, typ, window=window, hi=500, cross_len=333, batch=4, T=T)

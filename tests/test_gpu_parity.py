@@ -147,6 +147,28 @@ def test_other_page_sizes(T, dtype, D, G, window):
         r.close()
 
 
+@pytest.mark.parametrize("T,dtype,D,G,window", [
+    (1, "bf16", 128, 4, 0), (1, "f32", 64, 2, 37), (2, "bf16", 256, 2, 0), (4, "bf16", 64, 8, 0), (4, "f32", 128, 3, 21),
+    (24, "bf16", 128, 4, 0), (24, "bf16", 256, 2, 100), (12, "f32", 64, 5, 0), (48, "bf16", 64, 1, 0),
+    (3, "bf16", 128, 16, 50), (256, "bf16", 128, 2, 0), (20, "f32", 256, 4, 300)])
+def test_any_number_of_tokens_per_page(T, dtype, D, G, window):
+    """The paper leaves the page size open (Sec. 4.1 footnote: arbitrary; its figures use one token
+    per page): 1, 2 and 4 tokens, and sizes that are no power of two, through the engine mode in
+    which every lane looks up the page of the row it loads."""
+    print(f"[case] any T={T} {dtype} D={D} G={G} W={window}", flush=True)
+    # lengths up to 2500 tokens: with one token per page the page-id registers are refilled many times
+    cfg = custom_cfg(dtype, D, 2 * G, 2, WINDOW if window else FULL, window=window, hi=2500 if T < 8 else 1500, T=T,
+                     batch=4, n_layers=1)
+    for pps in (0, 7):
+        for fuse in (True, False):
+            r = _runner(cfg, 90 + T + D, pages_per_split=pps, fuse_append=fuse)
+            prepare(r)
+            r.device_step()
+            check_against_oracle(r, f"{cfg.name}/T{T}/pps{pps}")
+            check_append_landed(r)
+            r.close()
+
+
 @pytest.mark.parametrize("D,G,window,pps,T", [
     (128, 8, 0, 0, 16), (128, 8, 200, 2, 16), (128, 16, 0, 6, 16), (64, 8, 70, 0, 16), (64, 4, 0, 4, 16),
     (256, 8, 0, 0, 16), (256, 16, 33, 1, 16), (128, 1, 0, 2, 16), (64, 16, 0, 0, 16),

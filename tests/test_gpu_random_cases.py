@@ -15,7 +15,7 @@ def draw_case(seed):
     rng = np.random.default_rng(1000 + seed)
     dtype = rng.choice(["bf16", "bf16", "f32"])
     D = int(rng.choice([64, 128, 256]))
-    T = int(rng.choice([16, 16, 16, 8, 32, 64, 128]))
+    T = int(rng.choice([16, 16, 16, 8, 32, 64, 128, 1, 4, 24, 10]))
     G = int(rng.choice([1, 2, 4, 8, 16, 3, 5, 6, 7, 12]))
     Hkv = int(rng.choice([1, 2, 3]))
     window = int(rng.choice([0, 0, rng.integers(1, 400)]))

@@ -166,6 +166,34 @@ def test_kv_offset_matches_the_harness_address_map():
             assert int(nz[0]) // 4 * 4 == off
 
 
+def test_any_number_of_tokens_per_page_is_accepted():
+    """Sec. 4.1 footnote: tokens per page is arbitrary.  With one token per page and the footnote's
+    layer counts (3 self-attention layers, 2 cross-attention layers of 128 bytes per token) the small
+    pages are the figure's 384 and 256 bytes and the large page its 768."""
+    text = make_kind(J.FULL, J.BF16, 3, 1, 64, 1)      # 2 * 1 * 64 * 2 B = 256 B per token and layer ...
+    img = make_kind(J.CROSS, J.BF16, 2, 1, 64, 1)
+    # ... so the footnote's ratio 3 : 2 with a unit of 256 B instead of 128
+    assert J.lcm_page_bytes([text, img]) == 3 * 2 * 256
+    pool = J.Pool(None, 8 * 1536, [text, img])
+    assert pool.kind_stats(0).small_per_large == 2 and pool.kind_stats(1).small_per_large == 3
+    pool.request_extend(1, 0, 5)                       # five tokens: five pages
+    assert pool.request_block_table_row(1, 0, 6) == [0, 1, 2, 3, 4, -1]
+    for T in (1, 2, 3, 4, 10, 24, 100, 4096):
+        k = make_kind(J.WINDOW, J.F32, 2, 2, 64, T, window=50)
+        pool = J.Pool(None, 400 * J.lcm_page_bytes([k]), [k])
+        pool.request_extend(7, 0, 333)
+        row = pool.request_block_table_row(7, 0, 400)
+        n = -(-333 // T)
+        first = next(p for p in range(n) if T * (p + 1) > 333 - 50)
+        assert [s >= 0 for s in row[:n]] == [p >= first for p in range(n)] and all(s < 0 for s in row[n:])
+        assert pool.kv_offset(0, row[n - 1], 1, 1, 1, (333 - 1) % T) == \
+            row[n - 1] * 2 * (2 * 2 * T * 64 * 4) + 1 * (2 * 2 * T * 64 * 4) + 1 * (2 * T * 64 * 4) + T * 64 * 4 + ((333 - 1) % T) * 256
+        assert pool.decode_workspace_bytes(0, 4, 8, 400, window=50) > 0
+    for bad in (0, -2, 4097):
+        with pytest.raises(J.JengaError):
+            J.Pool(None, 1 << 20, [make_kind(J.FULL, J.BF16, 1, 2, 64, bad)])
+
+
 def test_error_paths():
     K = lambda s: make_kind(J.OPAQUE, small_page_bytes=s)
     with pytest.raises(J.JengaError) as e:
