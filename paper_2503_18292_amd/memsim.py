@@ -40,7 +40,30 @@ MODELS = {
                         n_kv_heads=8, head_dim=256, max_len=8192),
     "ministral_like": dict(kinds=[SimKind("full", api.FULL, 9), SimKind("window", api.WINDOW, 27, 32768)],
                            n_kv_heads=8, head_dim=128, max_len=131072),
+    # a small mix with uneven page sizes (2 : 3), for step-by-step comparisons of allocator front ends
+    "small_mix": dict(kinds=[SimKind("full", api.FULL, 2), SimKind("window", api.WINDOW, 3, 96)],
+                      n_kv_heads=2, head_dim=64, max_len=1024),
 }
+
+
+class LibraryFrontEnd:
+    """The library's allocator behind the three calls the simulation makes."""
+
+    def __init__(self, pool_bytes: int, kinds, large_page_bytes: int):
+        self.pool = Pool(None, pool_bytes, kinds, large_page_bytes)
+
+    def extend(self, request: int, kind: int, new_len: int) -> None:
+        self.pool.request_extend(request, kind, new_len)
+
+    def finish(self, request: int) -> None:
+        self.pool.request_free(request)
+
+    def owned_large_pages(self) -> int:
+        info = self.pool.get_info()
+        return info.n_large_pages - info.free_large_pages
+
+    def close(self) -> None:
+        self.pool.destroy()
 
 
 def make_trace(kind: str, n_requests: int, max_len: int, seed: int):
@@ -59,9 +82,12 @@ def make_trace(kind: str, n_requests: int, max_len: int, seed: int):
 
 
 def simulate(model: str, trace_kind: str, n_requests: int = 24, pool_gib: float = 0.0,
-             tokens_per_page: int = 16, seed: int = 0, sample_every: int = 16):
+             tokens_per_page: int = 16, seed: int = 0, sample_every: int = 16, front_end=None):
     """pool_gib <= 0: a pool that holds every request of the trace at its final length at once
-    (the simulation is about waste, not about running out of pages)."""
+    (the simulation is about waste, not about running out of pages).
+    front_end: a callable (pool_bytes, kind descriptors, large_page_bytes) -> object with
+    extend / finish / owned_large_pages / close; the library's allocator when None (the tests
+    pass a second implementation to compare the two step by step)."""
     m = MODELS[model]
     kinds = [make_kind(k.type, api.BF16, k.n_layers, m["n_kv_heads"], m["head_dim"], tokens_per_page, k.window)
              for k in m["kinds"]]
@@ -74,7 +100,7 @@ def simulate(model: str, trace_kind: str, n_requests: int = 24, pool_gib: float 
     else:
         final = sum(prompt + out_len + tokens_per_page for _, prompt, out_len in trace)
         pool_bytes = int(1.05 * final * n_layers * per_tok_layer) + 64 * large
-    pool = Pool(None, pool_bytes, kinds, large)
+    pool = (front_end or LibraryFrontEnd)(pool_bytes, kinds, large)
     horizon = max(a + o for a, _, o in trace) + 1
     length = {}                                   # live request -> cached tokens
     rows = []
@@ -86,24 +112,23 @@ def simulate(model: str, trace_kind: str, n_requests: int = 24, pool_gib: float 
                 length[rid] += 1                  # one decode step
             if rid in length:
                 for k in range(len(kinds)):
-                    pool.request_extend(rid, k, length[rid])
+                    pool.extend(rid, k, length[rid])
                 if step == arr + out_len:
-                    pool.request_free(rid)
+                    pool.finish(rid)
                     del length[rid]
         if step % sample_every and step != horizon - 1:
             continue
-        info = pool.get_info()
         needed = 0                                # bytes some layer still needs
         for L in length.values():
             for k in m["kinds"]:
                 needed += (min(L, k.window) if k.window else L) * k.n_layers * per_tok_layer
-        owned = (info.n_large_pages - info.free_large_pages) * large
+        owned = pool.owned_large_pages() * large
         ours_waste = owned - needed
         homo_alloc = sum(-(-L // tokens_per_page) * tokens_per_page for L in length.values()) * n_layers * per_tok_layer
         rows.append(dict(step=step, live=len(length), needed=needed, ours_allocated=owned,
                          ours_wasted=ours_waste, homogeneous_allocated=homo_alloc,
                          homogeneous_wasted=homo_alloc - needed))
-    pool.destroy()
+    pool.close()
     tot_need = sum(r["needed"] for r in rows)
     summary = dict(
         model=model, trace=trace_kind, requests=n_requests, large_page_bytes=large,
