@@ -24,13 +24,16 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E peak
-# HBM traffic of one decode_partial launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
-# each scaled by what the same counter reads for a plain copy of known size (summaries and
-# commands: profiles/decode_kernels_*_hbm_traffic.md).  Default workload: fetched bytes are
-# 1.004 x the algorithmic K/V bytes, written bytes 3.69e6 per launch (split-K records and the
-# appended rows).  Known for the workloads that were measured.
+# HBM traffic of one decode_partial launch.  NOT measured in this run (counters need the
+# profiler): derived from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this same program, each
+# counter scaled by what it reads for a plain copy of known size (summaries and commands:
+# profiles/decode_kernels_*_hbm_traffic.md).  roofline.traffic = fetch_over_algorithmic x the
+# run's algorithmic bytes per launch + write_bytes; roofline.traffic_source says so.
 MEASURED_TRAFFIC = {"gemma2_9b": {"fetch_over_algorithmic": 1.004, "write_bytes": 3.69e6},
-                    "long_5to1": {"fetch_over_algorithmic": 1.005, "write_bytes": 2.55e6}}
+                    "llama32_vision_11b": {"fetch_over_algorithmic": 1.0075, "write_bytes": 2.60e6},
+                    "jamba_like": {"fetch_over_algorithmic": 1.0043, "write_bytes": 4.75e6},
+                    "long_5to1": {"fetch_over_algorithmic": 1.0047, "write_bytes": 2.55e6},
+                    "short_b1024": {"fetch_over_algorithmic": 1.025, "write_bytes": 1.871e7}}
 
 
 def parse():
@@ -61,20 +64,46 @@ def parse():
     return ap.parse_args()
 
 
-def cpu_baseline(runner, budget_s: float):
+def host_info():
+    """What the CPU figures ran on: cores this process may use, and the CPU's name."""
+    try:
+        affinity = len(os.sched_getaffinity(0))
+    except AttributeError:
+        affinity = os.cpu_count() or 1
+    model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as f:
+            for ln in f:
+                if ln.lower().startswith("model name"):
+                    model = ln.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
+    return affinity, model
+
+
+def cpu_baseline(runner, budget_s: float, fast_budget_s: float = 8.0):
     """The fp64 oracle on the host cores, on (request, layer) slices gathered from the pool.
     `budget_s` bounds the wall-clock time of the whole leg (most of it goes into reading the
-    slices back and converting them to fp64); only the oracle's own time enters the rate."""
+    slices back and converting them to fp64); only the oracle's own time enters the rate.
+    `cores` is the number of cores the oracle kept busy (its CPU time over its wall-clock time,
+    rounded): its per-head matrix-vector products leave most BLAS threads idle.
+    A second figure, clearly labelled, comes from oracle/attn_threads.py (fp32, one task per
+    (request, KV head) on a thread pool) on slices of the same step, so that the CPU side of the
+    report is not only a deliberately plain loop."""
     import numpy as np
     import torch
     from oracle.attn import decode_attention_one
+    from oracle.attn_threads import decode_attention_threads
     try:
-        from threadpoolctl import threadpool_info
-        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        from threadpoolctl import threadpool_info, threadpool_limits
+        blas_threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
-        threads = 1
+        threadpool_limits = None
+        blas_threads = 1
+    affinity, cpu_model = host_info()
     torch.cuda.synchronize()
-    t_used, nbytes, n_units, toks = 0.0, 0, 0, 0
+    t_used, cpu_used, nbytes, n_units = 0.0, 0.0, 0, 0
     leg_t0 = time.perf_counter()
     per_kind = {}
     for ki, k in enumerate(runner.attn_kinds):
@@ -91,9 +120,10 @@ def cpu_baseline(runner, budget_s: float):
                 vis = int(runner.visible_tokens(k)[b])
                 Kd[:, :Kd.shape[1] - vis] = 0.0      # rows outside the window are never read by the oracle
                 Vd[:, :Vd.shape[1] - vis] = 0.0
-                t0 = time.perf_counter()
+                t0, c0 = time.perf_counter(), time.process_time()
                 decode_attention_one(q[b], Kd, Vd, runner.scale(k), kd.window)
                 dt = time.perf_counter() - t0
+                cpu_used += time.process_time() - c0
                 t_used += dt
                 t_kind += dt
                 b_kind += vis * kd.bytes_per_token_per_layer
@@ -109,8 +139,11 @@ def cpu_baseline(runner, budget_s: float):
     for k, (t_kind, b_kind, n_kind) in per_kind.items():
         if b_kind:
             step_s += t_kind * runner.kv_bytes_layer(k) / b_kind * runner.cfg.kinds[k].n_layers
-    return {
-        "value": round(gbs, 4), "unit": "GB/s", "cores": int(threads), "kind": "oracle",
+    out = {
+        "value": round(gbs, 4), "unit": "GB/s", "cores": max(1, int(round(cpu_used / t_used))) if t_used > 0 else 1,
+        "kind": "oracle",
+        "cores_note": "cores = CPU time / wall-clock time inside the oracle (what it kept busy)",
+        "host": {"cores_available": affinity, "cpu_model": cpu_model, "blas_threads": blas_threads},
         "sample": f"{n_units} (request, layer) slices of the same step, read back from the pool: layers then "
                   f"requests in order, each attention kind until its share of {budget_s:.0f} s of wall-clock "
                   f"time (read-back and conversion included) is used; fp64 numpy, {t_used:.1f} s inside the oracle; "
@@ -118,6 +151,40 @@ def cpu_baseline(runner, budget_s: float):
                   f"layer count: {step_s:.1f} s/step = {runner.cfg.batch / step_s if step_s else 0:.3f} tokens/s",
         "seconds": round(t_used, 2),
     }
+    # second figure: fp32, one task per (request, KV head) on all available cores; batches of
+    # requests of layer 0 of each kind until the budget is used
+    fast_t, fast_bytes, fast_n = 0.0, 0, 0
+    fast_t0 = time.perf_counter()
+    threads = max(1, affinity)
+    limit = threadpool_limits(limits=1) if threadpool_limits else None    # the pool's threads are the parallelism
+    try:
+        for k in runner.attn_kinds:
+            kd = runner.cfg.kinds[k]
+            q32 = runner.inputs[(k, 0)][0].cpu().float().numpy()
+            b0 = 0
+            while b0 < runner.cfg.batch and time.perf_counter() - fast_t0 < fast_budget_s:
+                bs = list(range(b0, min(runner.cfg.batch, b0 + 2 * threads)))
+                Ks, Vs = [], []
+                for b in bs:
+                    K, V = runner.gather(k, 0, b)
+                    Ks.append(K.float().numpy())
+                    Vs.append(V.float().numpy())
+                t0 = time.perf_counter()
+                decode_attention_threads(q32[bs], Ks, Vs, runner.scale(k), kd.window, threads)
+                fast_t += time.perf_counter() - t0
+                fast_bytes += sum(int(runner.visible_tokens(k)[b]) for b in bs) * kd.bytes_per_token_per_layer
+                fast_n += len(bs)
+                b0 += len(bs)
+    finally:
+        if limit is not None:
+            limit.restore_original_limits() if hasattr(limit, "restore_original_limits") else limit.unregister()
+    out["fp32_threaded"] = {
+        "value": round(fast_bytes / fast_t / 1e9, 3) if fast_t > 0 else 0.0, "unit": "GB/s", "cores": threads,
+        "kind": "oracle/attn_threads.py: fp32, one task per (request, KV head) on a thread pool (not the parity oracle)",
+        "sample": f"{fast_n} (request, layer 0) slices of the same step within {fast_budget_s:.0f} s of wall-clock time "
+                  f"(read-back and conversion included, {fast_t:.2f} s inside the computation)",
+    }
+    return out
 
 
 def stream_read_rate(pool_u8, nbytes: int = 8 << 30, reps: int = 5) -> float:
@@ -373,6 +440,11 @@ def main():
             "traffic": (round(MEASURED_TRAFFIC[cfg.name]["fetch_over_algorithmic"] * k_bytes / n_launch
                               + MEASURED_TRAFFIC[cfg.name]["write_bytes"])
                         if cfg.name in MEASURED_TRAFFIC and args.pages_per_split == 0 else None),
+            "traffic_source": (f"profiles/decode_kernels_{cfg.name}_hbm_traffic.md (rocprofv3 --pmc FETCH_SIZE, "
+                               f"WRITE_SIZE, copy-calibrated): fetched = "
+                               f"{MEASURED_TRAFFIC[cfg.name]['fetch_over_algorithmic']} x algorithmic, "
+                               f"written = {MEASURED_TRAFFIC[cfg.name]['write_bytes']:.3g} B per launch"
+                               if cfg.name in MEASURED_TRAFFIC and args.pages_per_split == 0 else None),
             "per_kind_GBps": {cfg.kinds[k].name: round(per_kind_bytes[k] / (per_kind_ms[k] * 1e-3) / 1e9, 1)
                               for k in r.attn_kinds},
         })

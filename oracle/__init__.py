@@ -10,4 +10,6 @@ library or its Python binding, and imports neither.
             (paper Sec. 4.1, 4.3; sliding-window need set of Sec. 5.1).
   attn.py   dense masked softmax attention over contiguous K/V in fp64
             (the textbook definition; the window of Sec. 5.1, Fig. last-access).
+  attn_threads.py  the same computation in fp32 on a thread pool: a second, faster CPU
+            figure for the benchmark's report, pinned against attn.py; never the reference.
 """

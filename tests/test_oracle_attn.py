@@ -191,3 +191,18 @@ def test_batch_wrapper_and_empty():
         assert np.array_equal(out[b], decode_attention_one(q[b], Ks[b], Vs[b], 0.5, 4))
     empty = decode_attention_one(q[0], np.zeros((2, 0, 8)), np.zeros((2, 0, 8)), 0.5, 0)
     assert np.array_equal(empty, np.zeros((4, 8)))
+
+
+def test_threaded_fp32_baseline_agrees_with_the_oracle():
+    """The second CPU baseline of the benchmark's report computes what the oracle computes."""
+    from oracle.attn_threads import decode_attention_threads
+    rng = np.random.default_rng(11)
+    for window in (0, 37):
+        lens = [1, 5, 64, 300, 1000]
+        q = rng.normal(size=(len(lens), 8, 64)).astype(np.float32)
+        Ks = [rng.normal(size=(2, L, 64)).astype(np.float32) for L in lens]
+        Vs = [rng.normal(size=(2, L, 64)).astype(np.float32) for L in lens]
+        got = decode_attention_threads(q, Ks, Vs, 0.125, window, threads=3)
+        for b in range(len(lens)):
+            want = decode_attention_one(q[b], Ks[b], Vs[b], 0.125, window)
+            assert np.abs(got[b] - want).max() <= 2e-6
