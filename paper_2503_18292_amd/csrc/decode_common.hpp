@@ -77,6 +77,42 @@ __device__ __forceinline__ int units_of(int L, int window, int t_log2, int tile_
   return kSegStartUnits + ((first_token_of(t_log2, p_hi - p_lo) + (1 << tile_log2) - 1) >> tile_log2);
 }
 
+// R rounds of 64 requests (see scan_requests); rounds past the batch hold no request.
+template <int R, class Units>
+__device__ __forceinline__ int scan_rounds(const int32_t* seq_lens, int batch, int lane,
+                                           int* s_incl, int* s_len, Units units) {
+  int raw[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const int i = r * kWave + lane;
+    raw[r] = i < batch ? seq_lens[i] : 0;
+  }
+  int incl[R], enc[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) incl[r] = units(raw[r], &enc[r]);
+#pragma unroll
+  for (int off = 1; off < kWave; off <<= 1) {
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const int up = __shfl_up(incl[r], off);
+      if (lane >= off) incl[r] += up;
+    }
+  }
+  int carry = 0;
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    const int i = r * kWave + lane;
+    incl[r] += carry;
+    if (i < batch) {
+      s_incl[i] = incl[r];
+      s_len[i] = enc[r];
+    }
+    carry = __builtin_amdgcn_readlane(incl[r], kWave - 1);
+  }
+  __syncthreads();
+  return carry;
+}
+
 // Inclusive prefix sums of units * n_kv_heads per request into LDS, lengths next to them: the
 // length the kernels work with is min(seq_lens[i], max_seq_len), stored negated when the clamp
 // took effect (such a request is attended over its first max_seq_len tokens, and its new row,
@@ -107,41 +143,13 @@ __device__ __forceinline__ int scan_requests(const int32_t* seq_lens, int batch,
     __syncthreads();
     return __builtin_amdgcn_readlane(incl, kWave - 1);
   }
-  // Larger batches: lane l takes the K = ceil(batch / 64) consecutive requests l*K .. l*K + K - 1.
-  // All their lengths are requested before any is used (one memory round trip instead of one per
-  // 64 requests: 7.5 us -> 1.6 us at batch 1024), each lane sums its own, one wave scan of the
-  // lane totals follows.
+  // Larger batches, 64 requests a round: lane l of round r takes request 64 r + l, so a round's
+  // lengths are one coalesced 256-byte load.  All rounds are requested before any is used (one
+  // memory round trip), each is scanned over the wavefront on its own (the scans do not depend on
+  // one another, so they overlap), and the rounds' totals are carried along at the end.
   const int K = (batch + kWave - 1) / kWave;
-  int raw[kRounds];
-#pragma unroll
-  for (int r = 0; r < kRounds; ++r) {
-    const int i = lane * K + r;
-    raw[r] = (r < K && i < batch) ? seq_lens[i] : 0;
-  }
-  int own[kRounds], enc[kRounds];
-  int total = 0;
-#pragma unroll
-  for (int r = 0; r < kRounds; ++r) {
-    total += units(raw[r], &enc[r]);
-    own[r] = total;
-  }
-  int incl = total;
-#pragma unroll
-  for (int off = 1; off < kWave; off <<= 1) {
-    const int up = __shfl_up(incl, off);
-    if (lane >= off) incl += up;
-  }
-  const int before = incl - total;
-#pragma unroll
-  for (int r = 0; r < kRounds; ++r) {
-    const int i = lane * K + r;
-    if (r < K && i < batch) {
-      s_incl[i] = before + own[r];
-      s_len[i] = enc[r];
-    }
-  }
-  __syncthreads();
-  return __builtin_amdgcn_readlane(incl, kWave - 1);
+  if (K <= 4) return scan_rounds<4>(seq_lens, batch, lane, s_incl, s_len, units);
+  return scan_rounds<kRounds>(seq_lens, batch, lane, s_incl, s_len, units);
 }
 
 __device__ __forceinline__ int chunk_of(int chunk_tiles, int min_chunk_tiles, int W, int n_part) {

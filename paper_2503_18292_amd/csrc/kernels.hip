@@ -163,14 +163,17 @@ __global__ __launch_bounds__(kWave) void decode_partial_kernel(const DecodeParam
   int x = int(x0);
   const int x1 = int(min<int64_t>(W, x0 + C));
   int b = BIG ? find_request_global(incl, p.batch, x, lane) : find_request(incl, p.batch, x, lane);
-  while (x < x1) {
-    // x only grows: the request of the next segment is the same one or a later one
-    while (b < p.batch - 1 && incl[b] <= x) ++b;
+  // The segments of a chunk follow one another: after the first one, (request, KV head) moves on
+  // by one head, or to the next request that has tokens.  Only the first needs a division.
+  int L_enc = lens[b];
+  int units_b = units_of(abs(L_enc), p.window, p.t_log2, Eng::kTileLog2);   // start-up units + tiles, per head
+  int kvh, seg0;                                                            // seg0: flat position of the segment
+  {
     const int start_b = b > 0 ? incl[b - 1] : 0;
-    const int units_b = (incl[b] - start_b) / p.n_kv_heads;       // start-up units + tiles, per head
-    const int rem = x - start_b;
-    const int kvh = rem / units_b;
-    const int seg0 = start_b + kvh * units_b;                     // flat position of the segment
+    kvh = (x - start_b) / units_b;
+    seg0 = start_b + kvh * units_b;
+  }
+  while (x < x1) {
     const int xe = min(x1, seg0 + units_b);
     // tiles of the segment inside [x, xe): none if the chunk ends inside the start-up units
     const int tile0 = max(x - seg0 - kSegStartUnits, 0);
@@ -179,7 +182,9 @@ __global__ __launch_bounds__(kWave) void decode_partial_kernel(const DecodeParam
       const int seg = b * p.n_kv_heads + kvh;
       const int slot = seg + int(blockIdx.x);
       // the wavefront that holds a segment's first tile tells the reduction where its records are
-      const int last_chunk = (seg0 + units_b - 1) / C;
+      // (a segment whose tiles all lie in this chunk ends in it: no division)
+      const bool whole = tile0 == 0 && n_tiles == units_b - kSegStartUnits;
+      const int last_chunk = whole ? int(blockIdx.x) : (seg0 + units_b - 1) / C;
       // (the last record of a wavefront has nothing behind it to delay: it goes straight out)
       float* rec = nullptr;
       if (rec_cap > 0 && xe < x1) {
@@ -189,10 +194,9 @@ __global__ __launch_bounds__(kWave) void decode_partial_kernel(const DecodeParam
         }
         rec = s_rec + n_rec * rec_stride;
         if (lane == 0) {
-          const bool whole = p.out != nullptr && tile0 == 0 && n_tiles == units_b - kSegStartUnits;
           s_rslot[n_rec] = slot;
           s_rseg[n_rec] = tile0 == 0 ? seg : -1;
-          s_rlast[n_rec] = whole ? -1 : last_chunk;
+          s_rlast[n_rec] = whole && p.out != nullptr ? -1 : last_chunk;
         }
         ++n_rec;
       } else if (tile0 == 0 && lane == 0) {
@@ -200,7 +204,6 @@ __global__ __launch_bounds__(kWave) void decode_partial_kernel(const DecodeParam
       }
       // fused append: the chunk that holds the tile of the newest token (position L - 1) writes it
       // (not for a request whose length was clamped to max_seq_len: see scan_requests)
-      const int L_enc = lens[b];
       const int L = abs(L_enc);
       int append_tile = -1;
       if (p.k_new != nullptr && L_enc > 0) {
@@ -212,6 +215,15 @@ __global__ __launch_bounds__(kWave) void decode_partial_kernel(const DecodeParam
       Eng::run(p, lane, b, kvh, L, tile0, n_tiles, append_tile, slot, rec, ids, s_eng);
     }
     x = xe;
+    if (x < x1) {                                   // the segment ended inside the chunk
+      seg0 = x;
+      if (++kvh == p.n_kv_heads) {
+        kvh = 0;
+        do ++b; while (b < p.batch - 1 && incl[b] <= x);          // requests without tokens take no units
+        L_enc = lens[b];
+        units_b = units_of(abs(L_enc), p.window, p.t_log2, Eng::kTileLog2);
+      }
+    }
   }
   if (n_rec > 0) flush_records<Eng::D>(p, s_rec, s_rslot, s_rseg, s_rlast, n_rec, G, rec_stride, lane);
 }
