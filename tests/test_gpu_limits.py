@@ -19,6 +19,9 @@ MAX_BATCH = 1024      # the largest batch whose prefix sums are made per block, 
     (MAX_BATCH, 32, "f32", 64, 2, 40),       # fp32 K/V, 32-token pages, sliding window
     (65, 16, "bf16", 256, 2, 0),             # 512-byte rows, one page per tile; one request past a full round of the length scan
     (200, 16, "f32", 64, 1, 0),
+    (256, 16, "bf16", 128, 4, 0),            # the last batch of the four-round form of the length scan
+    (257, 8, "bf16", 64, 4, 0),              # the first of the sixteen-round form, 8-token pages
+    (777, 16, "f32", 128, 2, 30),            # a ragged last round
 ])
 def test_large_batches(batch, T, dtype, D, G, window):
     print(f"[case] batch={batch} T={T} {dtype} D={D} G={G} W={window}", flush=True)
