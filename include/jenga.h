@@ -341,6 +341,8 @@ int jenga_splitk_reduce(const jenga_pool* pool, int32_t kind, int32_t n_q_heads,
  * Every call on one GPU uses that GPU's buffer: calls that may overlap on one GPU (different
  * streams, or graphs replayed concurrently) race and must be serialised by the caller.  Nothing
  * in the buffer has to start at zero; each call overwrites what it reads.
+ * The buffer's address on a GPU is looked up once, when the first pool is created with that GPU
+ * current (else by the first call there, which should then not run under stream capture).
  * Further errors: HIP (no current device, or the buffer's address cannot be found). */
 int jenga_paged_decode_static(const jenga_pool* pool, int32_t kind, int32_t layer,
                               const void* q, int32_t n_q_heads,

@@ -539,6 +539,14 @@ void* static_scratch(int* rc) {
   return g_scratch_ptr[dev];
 }
 
+// The address is looked up when a pool is created on the device, so that the first
+// jenga_paged_decode_static call (which may run under stream capture) finds it there.
+void setup_device() noexcept {
+  int rc = JENGA_OK;
+  (void)static_scratch(&rc);
+}
+const bool g_setup_hook_set = (jenga::device_setup_hook = &setup_device, true);
+
 // ---- host side: validation, partition geometry, launch --------------------------------
 
 using DecodeFn = void (*)(DecodeParams);

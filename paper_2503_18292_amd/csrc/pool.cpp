@@ -14,6 +14,10 @@
 using jenga::Kind;
 using jenga::RequestPages;
 
+namespace jenga {
+void (*device_setup_hook)() noexcept = nullptr;
+}
+
 namespace {
 
 bool is_attention(int32_t type) {
@@ -353,6 +357,7 @@ int jenga_pool_create(void* device_base, int64_t pool_bytes, int64_t large_page_
   p->large_cached.assign(size_t(p->n_large), 0);
   p->evictable_large_key.assign(size_t(p->n_large), std::make_tuple(int64_t(0), int64_t(0), int64_t(-1)));
   for (int64_t i = 0; i < p->n_large; ++i) p->free_large.insert(p->free_large.end(), i);
+  if (device_base != nullptr && jenga::device_setup_hook != nullptr) jenga::device_setup_hook();
   *out = p.release();
   return JENGA_OK;
   });

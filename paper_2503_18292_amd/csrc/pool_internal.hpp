@@ -40,6 +40,11 @@ struct Kind {
   int64_t cached_small = 0;
 };
 
+// Set by the kernel half of the library when it is linked in (the allocator also builds alone, for
+// host-only checks): per-device set-up that should not wait for the first decode call, run by
+// jenga_pool_create for a pool that lies in device memory.  Failures are left to that first call.
+extern void (*device_setup_hook)() noexcept;
+
 struct RequestPages {
   std::vector<std::vector<int32_t>> pages;   // [kind][logical page] -> small id or -1
   std::vector<int64_t> first_resident;       // [kind] every page below it is already -1

@@ -76,3 +76,44 @@ def test_static_scratch_limit_is_reported():
     assert e.value.status == -4          # JENGA_ERR_WORKSPACE
     torch.cuda.synchronize()
     r.close()
+
+
+def test_static_entry_point_in_a_hip_graph():
+    """What the entry point is for: captured into a HIP graph (where nothing may be allocated) and
+    replayed, with eager work and synchronisations between the replays, it gives the result of the
+    eager workspace call every time, append included."""
+    cfg = custom_cfg("bf16", 128, 8, 2, FULL, batch=6, lo=300, hi=3000, n_layers=2)
+    r = _runner(cfg, 91)
+    prepare(r)
+    r.device_step()                                        # eager, workspace entry point, append fused
+    torch.cuda.synchronize()
+    check_against_oracle(r, "eager")
+    eager = {key: v.clone() for key, v in r.out.items()}
+    pool_after = r.pool_u8.clone()
+
+    def static_step():
+        for k, layer in r.schedule:
+            kd = r.cfg.kinds[k]
+            q, k_new, v_new = r.inputs[(k, layer)]
+            r.pool.paged_decode_static(k, layer, q, r.tables[k], r.seq_lens[k], r.max_len[k], kd.window,
+                                       r.scale(k), r.out[(k, layer)], 0, k_new, v_new)
+
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            static_step()
+    torch.cuda.current_stream().wait_stream(side)
+    other = torch.zeros(1 << 20, device=r.device)
+    for rep in range(3):
+        for v in r.out.values():
+            v.fill_(float("nan"))
+        other.add_(1.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for key in eager:
+            assert torch.equal(r.out[key], eager[key]), f"replay {rep} layer {key}"
+        assert torch.equal(r.pool_u8, pool_after)          # the appended rows are the same rows
+    r.close()
