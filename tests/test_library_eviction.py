@@ -14,7 +14,8 @@ import paper_2503_18292_amd as J
 from paper_2503_18292_amd import api
 from paper_2503_18292_amd.api import make_kind
 
-from test_oracle_eviction import run_last_access_example
+from test_oracle_eviction import (evictable_large_page_beats_another_requests_empty_slot,
+                                  run_last_access_example, small_pages_of_equal_age)
 
 GOLD = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "paper_examples.json")))
 
@@ -91,6 +92,16 @@ def test_mixed_large_page_is_not_evicted_as_a_whole():
     got = script(LibAsOracle(opaque_pool(3, [256, 1024])))
     assert got == want
     assert want[5] == (2, []) and want[6] == "oom" and want[8] == (0, [(0, 0), (0, 1), (0, 2), (0, 3)])
+
+
+def test_step_order_and_tie_scenarios_match_the_oracle():
+    want = evictable_large_page_beats_another_requests_empty_slot(OracleCachingPool(3 * 1024, [256, 1024]))
+    got = evictable_large_page_beats_another_requests_empty_slot(LibAsOracle(opaque_pool(3, [256, 1024])))
+    assert (got[0], got[1], got[2]) == (want[0], want[1], want[2])
+    assert got[3][0] == want[3][0] and sorted(got[3][1]) == sorted(want[3][1])
+    want = small_pages_of_equal_age(OracleCachingPool(1024, [256], 1024))
+    pool = J.Pool(None, 1024, [make_kind(J.OPAQUE, small_page_bytes=256)], large_page_bytes=1024)
+    assert small_pages_of_equal_age(LibAsOracle(pool)) == want
 
 
 @pytest.mark.parametrize("seed,sizes,n_large", [(1, [256, 384], 10), (2, [64, 64], 24), (3, [2048, 3072, 6144], 8),

@@ -335,6 +335,35 @@ def test_resident_window_pages_are_exactly_those_touching_the_window(W, T):
     assert pool.free_large() == pool.n_large
 
 
+@pytest.mark.parametrize("T", [1, 16, 24])
+def test_a_partly_filled_last_page_is_a_page(T):
+    """Every cached token lies in a page (Sec. 4.2: a token is addressed by page id and offset in
+    the page): L tokens take ceil(L / T) pages, not floor, and growing inside a page takes none."""
+    pool = OraclePool(64 * 512, [512])
+    reqs = OracleRequests(pool, [T], [0])
+    want = 0
+    for L in (1, T, T + 1, 2 * T, 3 * T - 1 if T > 1 else 5, 3 * T + 1):
+        reqs.extend(7, 0, L)
+        want = max(want, (L + T - 1) // T)
+        assert pool.used_small(0) == want == len(reqs.row(7, 0, want))
+        assert all(x >= 0 for x in reqs.row(7, 0, want))
+
+
+def test_a_table_row_marks_what_is_not_resident():
+    """The block-table row of a request (Sec. 4.2, the per-type page list): its pages in logical
+    order, then -1 for every column past them, and -1 where a window page slid out -- never an id,
+    which would name a page that belongs to someone else."""
+    pool = OraclePool(16 * 512, [512])
+    reqs = OracleRequests(pool, [4], [6])             # 4 tokens per page, window of 6 tokens
+    reqs.extend(1, 0, 4)                              # another request holds page 0
+    reqs.extend(2, 0, 9)                              # pages 1, 2, 3
+    assert reqs.row(2, 0, 6) == [1, 2, 3, -1, -1, -1]
+    reqs.extend(2, 0, 14)                             # tokens 8..13 are needed: logical pages 0 and 1 slid out
+    assert reqs.row(2, 0, 6) == [-1, -1, 3, 4, -1, -1]
+    with pytest.raises(InvalidOp):
+        reqs.row(2, 0, 3)
+
+
 def test_share_prefix_and_free_order():
     pool = OraclePool(64 * 4096, [1024, 4096])
     reqs = OracleRequests(pool, [16, 16], [0, 0])

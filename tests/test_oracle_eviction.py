@@ -173,6 +173,43 @@ def test_large_page_is_evictable_only_when_all_its_small_pages_are():
     assert sid == 1 and sorted(ev) == [(0, s) for s in y]
 
 
+def evictable_large_page_beats_another_requests_empty_slot(pool):
+    """Sec. 5.4 orders the steps: an evictable large page is evicted (step 3) before an empty small
+    page associated with another request is taken (step 4)."""
+    x = [pool.alloc(0, 1) for _ in range(4)]          # large page 0, request 1
+    y = pool.alloc(0, 2)                              # large page 1, request 2: three empty slots left
+    z = pool.alloc(1, 3)                              # large page 2, the other kind: no empty large page left
+    for sid in x:
+        pool.set_last_access(0, sid, 4)
+        pool.release(0, sid, keep_cached=True)        # large page 0: all four evictable
+    got = pool.alloc_evict(0, 9)                      # request 9 owns nothing: steps 1 and 2 fail
+    return x, y, z, got
+
+
+def test_step_3_comes_before_step_4():
+    x, y, z, got = evictable_large_page_beats_another_requests_empty_slot(OracleCachingPool(3 * 1024, [256, 1024]))
+    assert (x, y, z) == ([0, 1, 2, 3], 4, 2)
+    sid, ev = got
+    assert sid == 0 and sorted(ev) == [(0, 0), (0, 1), (0, 2), (0, 3)]      # not slot 5 of request 2's page
+
+
+def small_pages_of_equal_age(pool):
+    """Sec. 5.1: among tokens of equal last access the one with the highest prefix length goes
+    first -- also when single small pages are evicted (step 5)."""
+    x = [pool.alloc(0, 1) for _ in range(4)]          # one large page; page x[0] stays in use
+    for sid, n in zip(x[1:], (2, 7, 4)):
+        pool.set_last_access(0, sid, 5)
+        pool.set_prefix_length(0, sid, n)
+        pool.release(0, sid, keep_cached=True)
+    return x, [pool.alloc_evict(0, 9) for _ in range(3)]
+
+
+def test_step_5_ties_go_to_the_longest_prefix():
+    x, got = small_pages_of_equal_age(OracleCachingPool(1024, [256], 1024))
+    assert x == [0, 1, 2, 3]
+    assert got == [(2, [(0, 2)]), (3, [(0, 3)]), (1, [(0, 1)])]            # prefix 7, then 4, then 2
+
+
 def test_large_page_lru_uses_latest_access_of_its_small_pages():
     pool = OracleCachingPool(2 * 1024, [256, 1024])
     x = [pool.alloc(0, 1) for _ in range(4)]          # large page 0
